@@ -1,0 +1,136 @@
+/* rosaq.h - C ABI of the MI355X (gfx950) fused ROSAQ linear layer.
+ *
+ * The layer is y = (x Q) What^T  with  What = W Q  stored in mixed precision:
+ * the K rotated input channels with the largest PCA eigenvalues stay FP16, all
+ * other channels are INT4 / INT3 codes in groups of 128 with an FP16 scale and an
+ * integer (FP16-stored) zero point per (output row, group).
+ *
+ * Notation.  The paper writes the rotation as R and weights as W in R^{d x d'};
+ * this interface names the rotation Q and takes weights in the PyTorch layout
+ * W[out, in] = W[N, D].  Hence What = W Q is the transpose of the paper's R^T W
+ * (Eq. 1-3), and "salient rows of R^T W" become salient columns of What.
+ *
+ * Conventions: every function returns 0 (ROSAQ_OK) or a negative error code and
+ * never throws or aborts; rosaq_last_error() gives the text of the last failure
+ * on the calling thread.  "HOST" / "DEVICE" say where a pointer must live.
+ * All fp16 data is passed as raw IEEE binary16 bit patterns (uint16_t).
+ */
+#ifndef ROSAQ_H_
+#define ROSAQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ROSAQ_OK             0
+#define ROSAQ_ERR_NULL      (-1)  /* a required pointer is NULL                                  */
+#define ROSAQ_ERR_SHAPE     (-2)  /* D % 128, (D-K) % group, K > D, M < 1, leading dim < width   */
+#define ROSAQ_ERR_ARG       (-3)  /* bits not 3/4, group != 128, head_dim != 128, bad enum       */
+#define ROSAQ_ERR_MODE      (-4)  /* entry point does not serve this handle's q_mode             */
+#define ROSAQ_ERR_ALIGN     (-5)  /* device pointer / leading dimension not 16-byte aligned      */
+#define ROSAQ_ERR_WORKSPACE (-6)  /* workspace missing or smaller than rosaq_workspace_bytes      */
+#define ROSAQ_ERR_NONFINITE (-7)  /* NaN / Inf in W, Q, eigenvalues or the rotated weights       */
+#define ROSAQ_ERR_HIP       (-8)  /* a HIP call failed (text in rosaq_last_error)                */
+#define ROSAQ_ERR_NOMEM     (-9)  /* host allocation failed                                      */
+#define ROSAQ_ERR_HOSTONLY  (-10) /* handle was packed with host_only and has no device buffers  */
+
+/* Rotation kinds.  NONE is R = I (the rotation-less "Mixed" baseline, Sec. 4.1);
+ * FULL is the layer-wise PCA rotation (Sec. 3.1, Eq. 4); HEADWISE is the block
+ * diagonal rotation made of one PCA per attention head (Sec. 3.1.1, Eq. 6). */
+#define ROSAQ_Q_NONE     0
+#define ROSAQ_Q_FULL     1
+#define ROSAQ_Q_HEADWISE 2
+
+typedef struct rosaq_packed rosaq_packed_t;   /* opaque; owns its host and device buffers */
+
+/* Description of one linear layer to pack (Sec. 3.1-3.3; Eq. 3).  All pointers HOST;
+ * the library copies what it needs, the caller may free them after the call. */
+typedef struct {
+  int32_t out_features;      /* N                                                             */
+  int32_t in_features;       /* D, multiple of 128                                            */
+  const uint16_t* W;         /* fp16 [N x D], row n at W + n*ldw                              */
+  int64_t ldw;               /* >= D, in elements                                             */
+  int32_t q_mode;            /* ROSAQ_Q_*                                                     */
+  int32_t head_dim;          /* 128 for HEADWISE, ignored otherwise                           */
+  const float* Q;            /* fp32. FULL: [D x D] row-major, xhat = x Q (eigenvectors are    */
+                             /* columns). HEADWISE: [D/128][128][128], block h rotates input   */
+                             /* channels 128h..128h+127. NONE: ignored (may be NULL)           */
+  const double* eigenvalues; /* [D], one per rotated channel: the saliency key (Sec. 3.2)      */
+  int32_t K;                 /* number of FP16 salient channels, multiple of 32, (D-K) % 128 == 0 */
+  int32_t bits;              /* 3 or 4                                                        */
+  int32_t group;             /* 128                                                           */
+  int32_t select_rule;       /* 0 = the K largest eigenvalues (ties: lower channel first)     */
+  int32_t host_only;         /* nonzero: build the canonical arrays only, touch no GPU         */
+} rosaq_pack_desc;
+
+/* rosaq_pack_weights - offline step of the method (Sec. 3.1-3.3, Eq. 1-3):
+ *   1. What = W Q in fp64, rounded once to fp16 (HEADWISE: per 128-column block);
+ *   2. salient_idx = the K channels with the largest eigenvalues, ascending;
+ *      storage order perm = [salient_idx ; all other channels ascending];
+ *   3. W_S = What[:, salient_idx] kept as fp16;
+ *   4. the other columns, in storage order, are cut into groups of 128 and each
+ *      (row, group) is quantised:  s = fp16(max((max-min)/(2^bits-1), 2^-14)),
+ *      z = clamp(rne(-min/s), 0, 2^bits-1), q = clamp(rne(w/s)+z, 0, 2^bits-1)
+ *      (fp64 arithmetic, round-half-to-even; the paper fixes only "per-group,
+ *      128 channels, INT3/INT4": this formula is this library's reading);
+ *   5. unless host_only, device copies in the kernels' fragment order (plus an
+ *      fp16 copy of Q) are uploaded on `hip_stream` and the call waits for them.
+ * hip_stream is a hipStream_t (NULL = default stream).  *out is owned by the
+ * library until rosaq_free.  Errors: NULL, SHAPE, ARG, NONFINITE, NOMEM, HIP. */
+int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_packed_t** out);
+
+/* Bytes of DEVICE workspace rosaq_linear* needs for M rows (0 on a bad handle). */
+size_t rosaq_workspace_bytes(const rosaq_packed_t* p, int32_t M);
+
+/* rosaq_linear - Eq. 3 for q_mode NONE or FULL:
+ *     xhat = x fp16(Q)            (FULL; fp32 accumulate, xhat rounded to fp16)
+ *     y = xhat[:, salient_idx] W_S^T + xhat[:, rest] ((q - z) s)^T
+ * fp32 accumulation, y rounded to fp16 (RNE).
+ *   x_dev  DEVICE fp16 [M x D], row m at x + m*ldx (ldx >= D, ldx % 8 == 0, 16-byte aligned base)
+ *   y_dev  DEVICE fp16 [M x N], row m at y + m*ldy (ldy >= N, ldy % 8 == 0, 16-byte aligned base)
+ *   ws_dev DEVICE scratch of at least rosaq_workspace_bytes(p, M), 256-byte aligned;
+ *          contents need not be preserved or initialised between calls
+ * Asynchronous on hip_stream; allocates nothing and never synchronises.  Calls on
+ * the same handle must not overlap in time (they share split-K counters).
+ * Errors: NULL, SHAPE, MODE (HEADWISE handle), ALIGN, WORKSPACE, HOSTONLY, HIP. */
+int rosaq_linear(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t ldx,
+                 void* y_dev, int64_t ldy, void* ws_dev, size_t ws_bytes, void* hip_stream);
+
+/* rosaq_linear_headwise - Eq. 6: the same layer with the block-diagonal
+ * rotation  xhat[:, 128h..128h+127] = x[:, 128h..128h+127] fp16(Q_h).
+ * Same arguments and rules as rosaq_linear; serves q_mode HEADWISE only. */
+int rosaq_linear_headwise(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t ldx,
+                          void* y_dev, int64_t ldy, void* ws_dev, size_t ws_bytes,
+                          void* hip_stream);
+
+/* Shape and storage facts of a handle (any output pointer may be NULL). */
+int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* K,
+                      int32_t* bits, int32_t* group, int32_t* q_mode,
+                      size_t* device_bytes /* packed weights + scales + fp16 Q on the GPU */);
+
+/* rosaq_packed_export - copy the canonical (layout-independent) arrays of Eq. 3 to
+ * HOST buffers; any pointer may be NULL to skip it.
+ *   salient_idx int32 [K]            ascending rotated-channel indices
+ *   W_S         fp16  [N x K]        row-major
+ *   codes       uint8 [N x (D-K)]    one code per byte, storage order
+ *   scales      fp16  [N x (D-K)/group]
+ *   zeros       fp16  [N x (D-K)/group]  (integer valued)                         */
+int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t* W_S,
+                        uint8_t* codes, uint16_t* scales, uint16_t* zeros);
+
+/* Tuning aid for benchmarks: key "splitk" (0 = heuristic) or "wpb" override the
+ * launch heuristics of later rosaq_linear* calls in this process. */
+int rosaq_tune(const char* key, int32_t value);
+
+void rosaq_free(rosaq_packed_t* p);
+
+/* Text of the last error on this thread ("" if none). */
+const char* rosaq_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROSAQ_H_ */

@@ -1,0 +1,157 @@
+"""ctypes binding of librosaq.so: argument marshalling only.
+
+Names mirror the C ABI in include/rosaq.h.  Device buffers are plain integer
+addresses (e.g. torch.Tensor.data_ptr()); host arrays are numpy arrays.  Nothing
+here computes: if the shared library is missing the import of this module's
+`lib()` fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+Q_NONE, Q_FULL, Q_HEADWISE = 0, 1, 2
+
+ERR_NAMES = {0: "OK", -1: "NULL", -2: "SHAPE", -3: "ARG", -4: "MODE", -5: "ALIGN",
+             -6: "WORKSPACE", -7: "NONFINITE", -8: "HIP", -9: "NOMEM", -10: "HOSTONLY"}
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librosaq.so")
+
+EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_linear", "rosaq_linear_headwise",
+            "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_free",
+            "rosaq_last_error"]
+
+
+class PackDesc(C.Structure):
+    _fields_ = [("out_features", C.c_int32), ("in_features", C.c_int32),
+                ("W", C.c_void_p), ("ldw", C.c_int64),
+                ("q_mode", C.c_int32), ("head_dim", C.c_int32),
+                ("Q", C.c_void_p), ("eigenvalues", C.c_void_p),
+                ("K", C.c_int32), ("bits", C.c_int32), ("group", C.c_int32),
+                ("select_rule", C.c_int32), ("host_only", C.c_int32)]
+
+
+class RosaqError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"rosaq error {ERR_NAMES.get(code, code)} ({code}): {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded shared library (built in-tree by paper_2506_13472_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2506_13472_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        L.rosaq_pack_weights.argtypes = [C.POINTER(PackDesc), vp, C.POINTER(vp)]
+        L.rosaq_pack_weights.restype = C.c_int
+        L.rosaq_workspace_bytes.argtypes = [vp, i32]
+        L.rosaq_workspace_bytes.restype = sz
+        for f in (L.rosaq_linear, L.rosaq_linear_headwise):
+            f.argtypes = [vp, vp, i32, i64, vp, i64, vp, sz, vp]
+            f.restype = C.c_int
+        L.rosaq_packed_info.argtypes = [vp] + [C.POINTER(i32)] * 6 + [C.POINTER(sz)]
+        L.rosaq_packed_info.restype = C.c_int
+        L.rosaq_packed_export.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.rosaq_packed_export.restype = C.c_int
+        L.rosaq_tune.argtypes = [C.c_char_p, i32]
+        L.rosaq_tune.restype = C.c_int
+        L.rosaq_free.argtypes = [vp]
+        L.rosaq_free.restype = None
+        L.rosaq_last_error.argtypes = []
+        L.rosaq_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def rosaq_last_error() -> str:
+    return lib().rosaq_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise RosaqError(rc, rosaq_last_error())
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class Packed:
+    """Owner of one rosaq_packed_t handle."""
+
+    def __init__(self, handle: int):
+        self.handle = C.c_void_p(handle)
+        n, d, k, b, g, m = (C.c_int32() for _ in range(6))
+        dev = C.c_size_t()
+        _check(lib().rosaq_packed_info(self.handle, n, d, k, b, g, m, dev))
+        self.N, self.D, self.K, self.bits, self.group, self.q_mode = (v.value for v in (n, d, k, b, g, m))
+        self.device_bytes = dev.value
+
+    def free(self):
+        if self.handle:
+            lib().rosaq_free(self.handle)
+            self.handle = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def rosaq_pack_weights(W: np.ndarray, Q, eigenvalues: np.ndarray, K: int, bits: int, q_mode: int,
+                       group: int = 128, head_dim: int = 128, select_rule: int = 0,
+                       host_only: bool = False, stream: int = 0, ldw: int | None = None,
+                       out_features: int | None = None, in_features: int | None = None) -> Packed:
+    """W fp16 [N, D]; Q fp32 ([D, D] or [H, 128, 128]) or None; eigenvalues fp64 [D]."""
+    W = None if W is None else np.ascontiguousarray(W, dtype=np.float16)
+    Qc = None if Q is None else np.ascontiguousarray(Q, dtype=np.float32)
+    lam = None if eigenvalues is None else np.ascontiguousarray(eigenvalues, dtype=np.float64)
+    d = PackDesc()
+    d.out_features = out_features if out_features is not None else (W.shape[0] if W is not None else 0)
+    d.in_features = in_features if in_features is not None else (W.shape[1] if W is not None else 0)
+    d.W = _ptr(W)
+    d.ldw = ldw if ldw is not None else d.in_features
+    d.q_mode, d.head_dim = q_mode, head_dim
+    d.Q, d.eigenvalues = _ptr(Qc), _ptr(lam)
+    d.K, d.bits, d.group, d.select_rule, d.host_only = K, bits, group, select_rule, int(host_only)
+    out = C.c_void_p()
+    _check(lib().rosaq_pack_weights(C.byref(d), C.c_void_p(stream), C.byref(out)))
+    return Packed(out.value)
+
+
+def rosaq_packed_export(p: Packed) -> dict:
+    G = (p.D - p.K) // p.group
+    sal = np.empty(p.K, np.int32)
+    W_S = np.empty((p.N, p.K), np.float16)
+    codes = np.empty((p.N, p.D - p.K), np.uint8)
+    scales = np.empty((p.N, G), np.float16)
+    zeros = np.empty((p.N, G), np.float16)
+    _check(lib().rosaq_packed_export(p.handle, _ptr(sal), _ptr(W_S), _ptr(codes), _ptr(scales), _ptr(zeros)))
+    return dict(salient_idx=sal, W_S=W_S, codes=codes, scales=scales, zeros=zeros)
+
+
+def rosaq_workspace_bytes(p: Packed, M: int) -> int:
+    return lib().rosaq_workspace_bytes(p.handle, M)
+
+
+def rosaq_linear(p: Packed, x_ptr: int, M: int, ldx: int, y_ptr: int, ldy: int, ws_ptr: int,
+                 ws_bytes: int, stream: int = 0):
+    _check(lib().rosaq_linear(p.handle, x_ptr, M, ldx, y_ptr, ldy, ws_ptr, ws_bytes, stream))
+
+
+def rosaq_linear_headwise(p: Packed, x_ptr: int, M: int, ldx: int, y_ptr: int, ldy: int, ws_ptr: int,
+                          ws_bytes: int, stream: int = 0):
+    _check(lib().rosaq_linear_headwise(p.handle, x_ptr, M, ldx, y_ptr, ldy, ws_ptr, ws_bytes, stream))
+
+
+def rosaq_tune(key: str, value: int):
+    _check(lib().rosaq_tune(key.encode(), value))

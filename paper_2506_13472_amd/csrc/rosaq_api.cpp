@@ -1,0 +1,284 @@
+// C ABI of the library: argument validation, handle ownership, device upload and
+// the per-call launch sequence.  No arithmetic of the method happens here.
+#include <hip/hip_runtime_api.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "rosaq_internal.h"
+
+namespace rosaq {
+
+static thread_local std::string g_error;
+void set_error(const std::string& s) { g_error = s; }
+
+static int g_tune_splitk = 0;  // 0 = heuristic
+static int g_tune_wpb = 0;     // 0 = default (4 waves per workgroup)
+
+static int fail(int code, const std::string& msg) {
+  set_error(msg);
+  return code;
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static int padded_tiles(int n) { return ((n + 127) / 128) * 8; }  // 16-channel tiles, whole 128s
+
+static int splits_for(int M, int N, int units) {
+  int s = g_tune_splitk > 0 ? g_tune_splitk : pick_splits(M, N, units);
+  return std::max(1, std::min(s, std::max(1, units)));
+}
+
+// Workspace carve-up for one call with M rows.
+struct WsPlan {
+  size_t xf_a = 0, xf_b = 0, part_main = 0, part_rot = 0, total = 0;
+  int s_main = 1, s_rot = 1;
+};
+
+static WsPlan plan_workspace(const rosaq_packed& p, int M) {
+  WsPlan w;
+  const Canonical& c = p.c;
+  const size_t mblocks = (static_cast<size_t>(M) + kMBlock - 1) / kMBlock;
+  const size_t xf_bytes = mblocks * (c.D / kKStep) * 4 * 64 * 16;
+  const size_t tile_bytes = 4 * 4 * 64 * 16;  // one 64 x 64 fp32 tile
+  w.s_main = splits_for(M, c.N, c.K / kKStep + c.G);
+  size_t off = 0;
+  w.xf_a = off; off += align_up(xf_bytes, 256);
+  if (c.q_mode == ROSAQ_Q_FULL) {
+    w.xf_b = off; off += align_up(xf_bytes, 256);
+    w.s_rot = splits_for(M, c.D, c.D / kKStep);
+  }
+  w.part_main = off;
+  if (w.s_main > 1) off += mblocks * (padded_tiles(c.N) / 4) * w.s_main * tile_bytes;
+  w.part_rot = off;
+  if (c.q_mode == ROSAQ_Q_FULL && w.s_rot > 1)
+    off += mblocks * (padded_tiles(c.D) / 4) * w.s_rot * tile_bytes;
+  w.total = off;
+  return w;
+}
+
+static int check_desc(const rosaq_pack_desc* d) {
+  if (!d) return fail(ROSAQ_ERR_NULL, "desc is NULL");
+  if (!d->W) return fail(ROSAQ_ERR_NULL, "desc.W is NULL");
+  if (!d->eigenvalues) return fail(ROSAQ_ERR_NULL, "desc.eigenvalues is NULL");
+  if (d->q_mode < ROSAQ_Q_NONE || d->q_mode > ROSAQ_Q_HEADWISE)
+    return fail(ROSAQ_ERR_ARG, "q_mode is not one of ROSAQ_Q_*");
+  if (d->q_mode != ROSAQ_Q_NONE && !d->Q) return fail(ROSAQ_ERR_NULL, "desc.Q is NULL");
+  if (d->bits != 3 && d->bits != 4) return fail(ROSAQ_ERR_ARG, "bits must be 3 or 4");
+  if (d->group != kGroup) return fail(ROSAQ_ERR_ARG, "group must be 128");
+  if (d->q_mode == ROSAQ_Q_HEADWISE && d->head_dim != kHeadDim)
+    return fail(ROSAQ_ERR_ARG, "head_dim must be 128");
+  if (d->select_rule != 0) return fail(ROSAQ_ERR_ARG, "select_rule must be 0");
+  if (d->out_features < 1 || d->in_features < 1)
+    return fail(ROSAQ_ERR_SHAPE, "out_features and in_features must be positive");
+  if (d->in_features % 128 != 0) return fail(ROSAQ_ERR_SHAPE, "in_features must be a multiple of 128");
+  if (d->K < 0 || d->K > d->in_features) return fail(ROSAQ_ERR_SHAPE, "K must be in [0, in_features]");
+  if (d->K % kKStep != 0) return fail(ROSAQ_ERR_SHAPE, "K must be a multiple of 32");
+  if ((d->in_features - d->K) % d->group != 0)
+    return fail(ROSAQ_ERR_SHAPE, "in_features - K must be a multiple of group");
+  if (d->ldw < d->in_features) return fail(ROSAQ_ERR_SHAPE, "ldw is smaller than in_features");
+  return ROSAQ_OK;
+}
+
+#define ROSAQ_HIP(call)                                                         \
+  do {                                                                          \
+    hipError_t e_ = (call);                                                     \
+    if (e_ != hipSuccess) {                                                     \
+      set_error(std::string(#call) + ": " + hipGetErrorString(e_));            \
+      return ROSAQ_ERR_HIP;                                                     \
+    }                                                                           \
+  } while (0)
+
+static int upload(rosaq_packed* p, const float* Q, hipStream_t st) {
+  DeviceImage img;
+  try {
+    build_device_image(p->c, Q, &img);
+  } catch (const std::bad_alloc&) { return fail(ROSAQ_ERR_NOMEM, "out of host memory"); }
+  const Canonical& c = p->c;
+  const size_t n_cnt_main = static_cast<size_t>(kMaxMBlocks) * (padded_tiles(c.N) / 4);
+  const size_t n_cnt_rot = static_cast<size_t>(kMaxMBlocks) * (padded_tiles(c.D) / 4);
+  p->counters_per_set = n_cnt_main;
+  struct Part { const void* src; size_t bytes; void** dst; };
+  void* d_cnt = nullptr;
+  void* d_perm = nullptr;
+  void* d_pos = nullptr;
+  Part parts[] = {
+      {img.wS.data(), img.wS.size() * 4, &p->d_wS},
+      {img.wq.data(), img.wq.size() * 4, &p->d_wq},
+      {img.sz.data(), img.sz.size() * 4, &p->d_sz},
+      {img.qf.data(), img.qf.size() * 4, &p->d_qf},
+      {c.perm.data(), c.perm.size() * 4, &d_perm},
+      {c.pos.data(), c.pos.size() * 4, &d_pos},
+      {nullptr, (n_cnt_main + n_cnt_rot) * 4, &d_cnt},
+  };
+  size_t total = 0;
+  for (const Part& q : parts) total += align_up(std::max<size_t>(q.bytes, 16), 256);
+  ROSAQ_HIP(hipGetDevice(&p->device));
+  ROSAQ_HIP(hipMalloc(&p->d_blob, total));
+  p->blob_bytes = total;
+  size_t off = 0;
+  for (const Part& q : parts) {
+    *q.dst = static_cast<char*>(p->d_blob) + off;
+    if (q.src && q.bytes) ROSAQ_HIP(hipMemcpyAsync(*q.dst, q.src, q.bytes, hipMemcpyHostToDevice, st));
+    else if (q.bytes) ROSAQ_HIP(hipMemsetAsync(*q.dst, 0, q.bytes, st));
+    off += align_up(std::max<size_t>(q.bytes, 16), 256);
+  }
+  ROSAQ_HIP(hipStreamSynchronize(st));   // staging vectors die with this frame
+  p->d_perm = static_cast<int32_t*>(d_perm);
+  p->d_pos = static_cast<int32_t*>(d_pos);
+  p->d_counters = static_cast<uint32_t*>(d_cnt);
+  p->host_only = false;
+  return ROSAQ_OK;
+}
+
+static int check_call(const rosaq_packed_t* p, const void* x, int32_t M, int64_t ldx, void* y,
+                      int64_t ldy, void* ws, size_t ws_bytes, bool headwise, WsPlan* plan) {
+  if (!p) return fail(ROSAQ_ERR_NULL, "handle is NULL");
+  if (!x || !y) return fail(ROSAQ_ERR_NULL, "x or y is NULL");
+  if ((p->c.q_mode == ROSAQ_Q_HEADWISE) != headwise)
+    return fail(ROSAQ_ERR_MODE, headwise ? "rosaq_linear_headwise needs a HEADWISE handle"
+                                         : "rosaq_linear does not serve a HEADWISE handle");
+  if (M < 1) return fail(ROSAQ_ERR_SHAPE, "M must be at least 1");
+  if (M > kMaxMBlocks * kMBlock) return fail(ROSAQ_ERR_SHAPE, "M above 4096: split the call");
+  if (ldx < p->c.D || ldy < p->c.N) return fail(ROSAQ_ERR_SHAPE, "leading dimension smaller than width");
+  if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16 || ldx % 8 || ldy % 8)
+    return fail(ROSAQ_ERR_ALIGN, "x, y must be 16-byte aligned and ldx, ldy multiples of 8");
+  *plan = plan_workspace(*p, M);
+  if (!ws || ws_bytes < plan->total) return fail(ROSAQ_ERR_WORKSPACE, "workspace missing or too small");
+  if (reinterpret_cast<uintptr_t>(ws) % 256) return fail(ROSAQ_ERR_ALIGN, "workspace must be 256-byte aligned");
+  if (p->host_only) return fail(ROSAQ_ERR_HOSTONLY, "handle was packed with host_only");
+  return ROSAQ_OK;
+}
+
+static int run_main_gemm(const rosaq_packed_t* p, const WsPlan& w, int M, void* y, int64_t ldy,
+                         char* ws, void* stream) {
+  const Canonical& c = p->c;
+  GemmArgs a{};
+  a.xf = ws + (c.q_mode == ROSAQ_Q_FULL ? w.xf_b : w.xf_a);
+  a.wS = p->d_wS; a.wq = p->d_wq; a.sz = p->d_sz;
+  a.partial = reinterpret_cast<float*>(ws + w.part_main);
+  a.counters = p->d_counters;
+  a.out = y; a.ldo = ldy; a.M = M; a.N = c.N;
+  a.ntiles = padded_tiles(c.N);
+  a.ks_s = c.K / kKStep; a.G = c.G; a.KS = c.D / kKStep; a.KS_out = 0;
+  a.bits = c.bits; a.splits = w.s_main; a.out_frag = 0;
+  return launch_gemm(a, g_tune_wpb, stream);
+}
+
+}  // namespace rosaq
+
+using namespace rosaq;
+
+extern "C" {
+
+int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_packed_t** out) {
+  if (!out) return fail(ROSAQ_ERR_NULL, "out is NULL");
+  *out = nullptr;
+  int rc = check_desc(desc);
+  if (rc != ROSAQ_OK) return rc;
+  rosaq_packed* p = new (std::nothrow) rosaq_packed();
+  if (!p) return fail(ROSAQ_ERR_NOMEM, "out of host memory");
+  std::string err;
+  try {
+    rc = pack_host(*desc, &p->c, &err);
+  } catch (const std::bad_alloc&) { rc = ROSAQ_ERR_NOMEM; err = "out of host memory"; }
+  if (rc != ROSAQ_OK) { delete p; return fail(rc, err); }
+  if (!desc->host_only) {
+    rc = upload(p, desc->Q, static_cast<hipStream_t>(hip_stream));
+    if (rc != ROSAQ_OK) { rosaq_free(p); return rc; }
+  }
+  *out = p;
+  return ROSAQ_OK;
+}
+
+size_t rosaq_workspace_bytes(const rosaq_packed_t* p, int32_t M) {
+  if (!p || M < 1) return 0;
+  return std::max<size_t>(plan_workspace(*p, M).total, 256);
+}
+
+int rosaq_linear(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t ldx, void* y_dev,
+                 int64_t ldy, void* ws_dev, size_t ws_bytes, void* hip_stream) {
+  WsPlan w;
+  int rc = check_call(p, x_dev, M, ldx, y_dev, ldy, ws_dev, ws_bytes, false, &w);
+  if (rc != ROSAQ_OK) return rc;
+  const Canonical& c = p->c;
+  char* ws = static_cast<char*>(ws_dev);
+  if (c.q_mode == ROSAQ_Q_NONE) {
+    rc = launch_gather(x_dev, ldx, M, c.D, p->d_perm, ws + w.xf_a, hip_stream);
+    if (rc != ROSAQ_OK) return rc;
+  } else {
+    // xhat = x fp16(Q): a dense fp16 contraction, run as an all-fp16 layer whose
+    // "weight" is Q^T with rows already in storage order
+    rc = launch_gather(x_dev, ldx, M, c.D, nullptr, ws + w.xf_a, hip_stream);
+    if (rc != ROSAQ_OK) return rc;
+    GemmArgs a{};
+    a.xf = ws + w.xf_a; a.wS = p->d_qf; a.wq = nullptr; a.sz = nullptr;
+    a.partial = reinterpret_cast<float*>(ws + w.part_rot);
+    a.counters = p->d_counters + p->counters_per_set;
+    a.out = ws + w.xf_b; a.ldo = 0; a.M = M; a.N = c.D;
+    a.ntiles = padded_tiles(c.D);
+    a.ks_s = c.D / kKStep; a.G = 0; a.KS = c.D / kKStep; a.KS_out = c.D / kKStep;
+    a.bits = 4; a.splits = w.s_rot; a.out_frag = 1;
+    rc = launch_gemm(a, g_tune_wpb, hip_stream);
+    if (rc != ROSAQ_OK) return rc;
+  }
+  return run_main_gemm(p, w, M, y_dev, ldy, ws, hip_stream);
+}
+
+int rosaq_linear_headwise(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t ldx,
+                          void* y_dev, int64_t ldy, void* ws_dev, size_t ws_bytes,
+                          void* hip_stream) {
+  WsPlan w;
+  int rc = check_call(p, x_dev, M, ldx, y_dev, ldy, ws_dev, ws_bytes, true, &w);
+  if (rc != ROSAQ_OK) return rc;
+  char* ws = static_cast<char*>(ws_dev);
+  rc = launch_rotate_headwise(x_dev, ldx, M, p->c.D, p->d_qf, p->d_pos, ws + w.xf_a, hip_stream);
+  if (rc != ROSAQ_OK) return rc;
+  return run_main_gemm(p, w, M, y_dev, ldy, ws, hip_stream);
+}
+
+int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* K, int32_t* bits,
+                      int32_t* group, int32_t* q_mode, size_t* device_bytes) {
+  if (!p) return fail(ROSAQ_ERR_NULL, "handle is NULL");
+  if (N) *N = p->c.N;
+  if (D) *D = p->c.D;
+  if (K) *K = p->c.K;
+  if (bits) *bits = p->c.bits;
+  if (group) *group = kGroup;
+  if (q_mode) *q_mode = p->c.q_mode;
+  if (device_bytes) *device_bytes = p->blob_bytes;
+  return ROSAQ_OK;
+}
+
+int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t* W_S, uint8_t* codes,
+                        uint16_t* scales, uint16_t* zeros) {
+  if (!p) return fail(ROSAQ_ERR_NULL, "handle is NULL");
+  const Canonical& c = p->c;
+  if (salient_idx) std::memcpy(salient_idx, c.salient_idx.data(), c.salient_idx.size() * 4);
+  if (W_S) std::memcpy(W_S, c.W_S.data(), c.W_S.size() * 2);
+  if (codes) std::memcpy(codes, c.codes.data(), c.codes.size());
+  if (scales) std::memcpy(scales, c.scales.data(), c.scales.size() * 2);
+  if (zeros) std::memcpy(zeros, c.zeros.data(), c.zeros.size() * 2);
+  return ROSAQ_OK;
+}
+
+int rosaq_tune(const char* key, int32_t value) {
+  if (!key) return fail(ROSAQ_ERR_NULL, "key is NULL");
+  if (!std::strcmp(key, "splitk")) { g_tune_splitk = value; return ROSAQ_OK; }
+  if (!std::strcmp(key, "wpb")) {
+    if (value != 0 && value != 4 && value != 8) return fail(ROSAQ_ERR_ARG, "wpb must be 0, 4 or 8");
+    g_tune_wpb = value; return ROSAQ_OK;
+  }
+  return fail(ROSAQ_ERR_ARG, "unknown tuning key");
+}
+
+void rosaq_free(rosaq_packed_t* p) {
+  if (!p) return;
+  if (p->d_blob) (void)hipFree(p->d_blob);
+  delete p;
+}
+
+const char* rosaq_last_error(void) { return g_error.c_str(); }
+
+}  // extern "C"

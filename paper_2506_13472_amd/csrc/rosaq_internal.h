@@ -1,0 +1,94 @@
+// Internal declarations shared by the host packer, the C ABI and the kernel launchers.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "rosaq.h"
+
+namespace rosaq {
+
+constexpr int kGroup = 128;    // quantisation group (Sec. 3.3: groups of 128 channels)
+constexpr int kHeadDim = 128;  // block size of the head-wise rotation (Eq. 6)
+constexpr int kKStep = 32;     // contraction depth of one v_mfma_f32_16x16x32_f16
+constexpr int kTileN = 16;     // output channels per MFMA tile
+constexpr int kMBlock = 64;    // rows of x handled by one workgroup pass (4 MFMA row tiles)
+constexpr int kMaxMBlocks = 64;  // split-K counters are provisioned for M <= 4096
+
+// ---- fp16 <-> fp64 on the host (rosaq_pack.cpp) -------------------------------
+uint16_t f64_to_f16(double v);  // round-half-to-even, one rounding, overflow -> inf
+double f16_to_f64(uint16_t h);
+
+// Host-side result of the offline step (Eq. 3): canonical arrays in storage order.
+struct Canonical {
+  int N = 0, D = 0, K = 0, bits = 0, q_mode = 0;
+  int G = 0;                          // low-bit groups per output row, (D-K)/128
+  std::vector<int32_t> salient_idx;   // [K] ascending
+  std::vector<int32_t> perm;          // [D] storage position -> rotated channel
+  std::vector<int32_t> pos;           // [D] rotated channel -> storage position
+  std::vector<uint16_t> W_S;          // [N x K] fp16
+  std::vector<uint8_t> codes;         // [N x (D-K)]
+  std::vector<uint16_t> scales;       // [N x G] fp16
+  std::vector<uint16_t> zeros;        // [N x G] fp16 (integer valued)
+};
+
+// Sec. 3.1-3.3 on the host.  Returns ROSAQ_OK or an error code with `err` filled.
+int pack_host(const rosaq_pack_desc& d, Canonical* out, std::string* err);
+
+// Device images (host staging copies) in the kernels' fragment order.
+struct DeviceImage {
+  std::vector<uint32_t> wS;   // [ntiles][K/32][64 lanes][4 dwords]   fp16 salient fragments
+  std::vector<uint32_t> wq;   // int4: [ntiles][G][64][4]; int3: [ntiles][G][64][3]
+  std::vector<uint32_t> sz;   // [ntiles][G][16]  scale | zero << 16
+  std::vector<uint32_t> qf;   // FULL: [D/16][D/32][64][4]; HEADWISE: [H][8][4][64][4]; fp16(Q)
+};
+void build_device_image(const Canonical& c, const float* Q, DeviceImage* img);
+
+// ---- kernel launchers (rosaq_kernels.hip) -------------------------------------
+struct GemmArgs {
+  const void* xf;        // xhat fragments  [mblocks][KS][4][64] x 16 B
+  const void* wS;        // fp16 fragments  [ntiles][ks_s][64]   x 16 B
+  const void* wq;        // low-bit fragments
+  const void* sz;        // scale/zero pairs
+  float* partial;        // split-K partial tiles
+  uint32_t* counters;    // one per (mblock, channel chunk), zero between calls
+  void* out;             // y (row-major fp16) or xhat fragments
+  int64_t ldo;           // leading dimension of y
+  int M, N;              // valid rows / output channels
+  int ntiles;            // ceil(N / 16)
+  int ks_s;              // fp16 k-steps (K/32)
+  int G;                 // low-bit groups
+  int KS;                // k-steps of the xf operand (D/32)
+  int KS_out;            // k-steps of the output when out is in fragment order
+  int bits;              // 3 or 4 (ignored when G == 0)
+  int splits;            // split-K factor S
+  int out_frag;          // 0: y row-major, 1: xhat fragment order
+};
+int launch_gemm(const GemmArgs& a, int wpb_override, void* stream);
+int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_dev,
+                  void* xf, void* stream);
+int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void* qh,
+                           const int32_t* pos_dev, void* xf, void* stream);
+int pick_splits(int M, int N, int units);
+
+void set_error(const std::string& s);
+
+}  // namespace rosaq
+
+struct rosaq_packed {
+  rosaq::Canonical c;
+  bool host_only = true;
+  int device = -1;
+  void* d_blob = nullptr;
+  size_t blob_bytes = 0;
+  // sub-buffers inside d_blob
+  void* d_wS = nullptr;
+  void* d_wq = nullptr;
+  void* d_sz = nullptr;
+  void* d_qf = nullptr;
+  int32_t* d_perm = nullptr;
+  int32_t* d_pos = nullptr;
+  uint32_t* d_counters = nullptr;   // two sets: rotation GEMM and main GEMM
+  size_t counters_per_set = 0;
+};

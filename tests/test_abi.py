@@ -1,0 +1,115 @@
+"""The C ABI without a GPU: symbols, argument validation, error codes."""
+import ctypes as C
+import re
+import os
+
+import numpy as np
+import pytest
+
+from paper_2506_13472_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "rosaq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(rosaq_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTED)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def _good(N=16, D=256, K=128, bits=4, mode=B.Q_NONE):
+    rng = np.random.default_rng(0)
+    W = (rng.standard_normal((N, D)) * 0.02).astype(np.float16)
+    lam = np.arange(D, 0, -1.0)
+    Q = None
+    if mode == B.Q_FULL:
+        Q = np.eye(D, dtype=np.float32)
+    elif mode == B.Q_HEADWISE:
+        Q = np.stack([np.eye(128, dtype=np.float32)] * (D // 128))
+    return W, Q, lam, K, bits, mode
+
+
+def _code(fn):
+    with pytest.raises(B.RosaqError) as e:
+        fn()
+    assert B.rosaq_last_error() != ""
+    return e.value.code
+
+
+def test_pack_argument_errors():
+    W, Q, lam, K, bits, mode = _good()
+    assert _code(lambda: B.rosaq_pack_weights(None, Q, lam, K, bits, mode, host_only=True,
+                                              out_features=16, in_features=256)) == -1
+    assert _code(lambda: B.rosaq_pack_weights(W, Q, None, K, bits, mode, host_only=True)) == -1
+    assert _code(lambda: B.rosaq_pack_weights(W, None, lam, K, bits, B.Q_FULL, host_only=True)) == -1
+    assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, K, 5, mode, host_only=True)) == -3
+    assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, K, bits, mode, group=64, host_only=True)) == -3
+    assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, K, bits, 7, host_only=True)) == -3
+    assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, K, bits, mode, select_rule=3, host_only=True)) == -3
+    Wh, Qh, lamh, *_ = _good(mode=B.Q_HEADWISE)
+    assert _code(lambda: B.rosaq_pack_weights(Wh, Qh, lamh, K, bits, B.Q_HEADWISE, head_dim=64,
+                                              host_only=True)) == -3
+    assert _code(lambda: B.rosaq_pack_weights(W[:, :200], Q, lam[:200], 72, bits, mode, host_only=True)) == -2
+    assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, 384, bits, mode, host_only=True)) == -2
+    assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, 64, bits, mode, host_only=True)) == -2
+    assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, K, bits, mode, ldw=100, host_only=True)) == -2
+    out = C.c_void_p()
+    assert B.lib().rosaq_pack_weights(None, None, C.byref(out)) == -1
+    d = B.PackDesc()
+    assert B.lib().rosaq_pack_weights(C.byref(d), None, None) == -1
+
+
+def test_pack_rejects_nonfinite():
+    W, Q, lam, K, bits, mode = _good()
+    Wb = W.copy(); Wb[3, 7] = np.inf
+    assert _code(lambda: B.rosaq_pack_weights(Wb, Q, lam, K, bits, mode, host_only=True)) == -7
+    lb = lam.copy(); lb[5] = np.nan
+    assert _code(lambda: B.rosaq_pack_weights(W, Q, lb, K, bits, mode, host_only=True)) == -7
+    Wf, Qf, lamf, *_ = _good(mode=B.Q_FULL)
+    Qb = Qf.copy(); Qb[0, 0] = np.nan
+    assert _code(lambda: B.rosaq_pack_weights(Wf, Qb, lamf, K, bits, B.Q_FULL, host_only=True)) == -7
+    Qo = Qf * np.float32(1e7)
+    assert _code(lambda: B.rosaq_pack_weights(Wf, Qo, lamf, K, bits, B.Q_FULL, host_only=True)) == -7
+
+
+def test_call_argument_errors_on_host_only_handle():
+    W, Q, lam, K, bits, mode = _good()
+    p = B.rosaq_pack_weights(W, Q, lam, K, bits, mode, host_only=True)
+    assert (p.N, p.D, p.K, p.bits, p.group, p.q_mode) == (16, 256, 128, 4, 128, 0)
+    assert p.device_bytes == 0
+    ws = B.rosaq_workspace_bytes(p, 4)
+    assert ws >= 256 and ws % 256 == 0
+    assert B.rosaq_workspace_bytes(p, 0) == 0
+    X, Y, WS = 0x1000, 0x2000, 0x4000      # never dereferenced: every call fails validation first
+    assert _code(lambda: B.rosaq_linear(p, 0, 4, 256, Y, 16, WS, ws)) == -1
+    assert _code(lambda: B.rosaq_linear(p, X, 0, 256, Y, 16, WS, ws)) == -2
+    assert _code(lambda: B.rosaq_linear(p, X, 5000, 256, Y, 16, WS, 1 << 40)) == -2
+    assert _code(lambda: B.rosaq_linear(p, X, 4, 128, Y, 16, WS, ws)) == -2
+    assert _code(lambda: B.rosaq_linear(p, X, 4, 256, Y, 8, WS, ws)) == -2
+    assert _code(lambda: B.rosaq_linear(p, X + 2, 4, 256, Y, 16, WS, ws)) == -5
+    assert _code(lambda: B.rosaq_linear(p, X, 4, 260, Y, 16, WS, ws)) == -5
+    assert _code(lambda: B.rosaq_linear(p, X, 4, 256, Y, 16, 0, ws)) == -6
+    assert _code(lambda: B.rosaq_linear(p, X, 4, 256, Y, 16, WS, ws - 1)) == -6
+    assert _code(lambda: B.rosaq_linear(p, X, 4, 256, Y, 16, WS + 16, ws)) == -5
+    assert _code(lambda: B.rosaq_linear_headwise(p, X, 4, 256, Y, 16, WS, ws)) == -4
+    assert _code(lambda: B.rosaq_linear(p, X, 4, 256, Y, 16, WS, ws)) == -10
+    Wh, Qh, lamh, *_ = _good(mode=B.Q_HEADWISE)
+    ph = B.rosaq_pack_weights(Wh, Qh, lamh, K, bits, B.Q_HEADWISE, host_only=True)
+    assert _code(lambda: B.rosaq_linear(ph, X, 4, 256, Y, 16, WS, 1 << 30)) == -4
+    assert _code(lambda: B.rosaq_linear_headwise(ph, X, 4, 256, Y, 16, WS, 1 << 30)) == -10
+    assert B.lib().rosaq_linear(None, X, 4, 256, Y, 16, WS, ws, None) == -1
+    assert B.lib().rosaq_packed_info(None, *([None] * 7)) == -1
+    assert B.lib().rosaq_packed_export(None, *([None] * 5)) == -1
+    B.lib().rosaq_free(None)
+    p.free(); ph.free()
+
+
+def test_tune_keys():
+    B.rosaq_tune("splitk", 0)
+    B.rosaq_tune("wpb", 0)
+    assert _code(lambda: B.rosaq_tune("wpb", 3)) == -3
+    assert _code(lambda: B.rosaq_tune("nope", 1)) == -3

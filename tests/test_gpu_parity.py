@@ -1,0 +1,131 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import rosaq_oracle as O
+from paper_2506_13472_amd import binding as B
+from paper_2506_13472_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+MAX_TOL = 2e-3      # max |y - y_ref| / (||x_row|| ||w_col||)
+FRO_TOL = 1e-3      # ||y - y_ref||_F / ||y_ref||_F
+
+
+def run_gpu(p, x16):
+    from paper_2506_13472_amd import torch_glue as T
+    x = torch.from_numpy(x16).cuda()
+    y = T.linear(p, x)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def check_output(y, x16, Q, ref):
+    y_ref = O.linear_ref(x16, Q, ref)
+    scale = O.tolerance_scale(x16, ref)
+    err = np.abs(y.astype(np.float64) - y_ref)
+    max_rel = float(np.max(err / scale))
+    fro = float(np.linalg.norm(err) / np.linalg.norm(y_ref))
+    print(f"  max_rel={max_rel:.3e} fro={fro:.3e}", flush=True)
+    assert np.all(np.isfinite(y))
+    assert max_rel <= MAX_TOL, max_rel
+    assert fro <= FRO_TOL, fro
+
+
+def check_pack(p, ref):
+    got = B.rosaq_packed_export(p)
+    for k in ("salient_idx", "W_S", "codes", "scales", "zeros"):
+        a, b = got[k], np.asarray(ref[k])
+        if a.dtype == np.float16:
+            a, b = a.view(np.uint16), b.astype(np.float16).view(np.uint16)
+        assert np.array_equal(a, b), k
+
+
+def make_case(seed, M, D, N, n_cal, mode, solver="jacobi"):
+    lay = synth.make_layer(seed, M, D, N, n_cal)
+    if mode == O.MODE_NONE:
+        Q, lam = None, np.abs(lay["X_cal"]).mean(axis=0)
+    elif mode == O.MODE_FULL:
+        Q, lam = O.pca_full(lay["X_cal"], solver)
+        Q = Q.astype(np.float32)
+    else:
+        Q, lam = O.pca_headwise(lay["X_cal"], 128, solver)
+        Q = Q.astype(np.float32)
+    return lay, Q, lam
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("mode", [O.MODE_NONE, O.MODE_HEADWISE, O.MODE_FULL])
+@pytest.mark.parametrize("M,D,N,K", [(4, 256, 48, 128), (64, 512, 200, 128), (37, 384, 130, 0),
+                                     (16, 256, 64, 256), (100, 512, 96, 128)])
+def test_small_shapes(bits, mode, M, D, N, K):
+    print(f"case bits={bits} mode={mode} M={M} D={D} N={N} K={K}", flush=True)
+    lay, Q, lam = make_case(100 + M, M, D, N, 300, mode)
+    ref = O.pack(lay["W"], Q, lam, K, bits, mode)
+    p = B.rosaq_pack_weights(lay["W"], Q, lam, K, bits, mode)
+    check_pack(p, ref)
+    y = run_gpu(p, lay["x"])
+    check_output(y, lay["x"], Q, ref)
+    p.free()
+
+
+def test_config0_single_linear():
+    """M=4, D=N=1024, full PCA rotation from 64 calibration rows, K=128, INT4 g128, seed 0."""
+    print("case config0", flush=True)
+    lay, Q, lam = make_case(0, 4, 1024, 1024, 64, O.MODE_FULL, solver="lapack")
+    ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_FULL)
+    assert ref["salient_idx"].tolist() == list(range(128))
+    p = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_FULL)
+    check_pack(p, ref)
+    y = run_gpu(p, lay["x"])
+    check_output(y, lay["x"], Q, ref)
+    p.free()
+
+
+@pytest.mark.parametrize("splitk", [1, 2, 3, 8])
+def test_split_k_variants_agree_with_oracle_and_are_deterministic(splitk):
+    print(f"case splitk={splitk}", flush=True)
+    lay, Q, lam = make_case(7, 64, 1024, 256, 512, O.MODE_HEADWISE)
+    ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_HEADWISE)
+    B.rosaq_tune("splitk", splitk)
+    try:
+        p = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_HEADWISE)
+        y0 = run_gpu(p, lay["x"])
+        check_output(y0, lay["x"], Q, ref)
+        for _ in range(5):
+            assert np.array_equal(run_gpu(p, lay["x"]).view(np.uint16), y0.view(np.uint16))
+        p.free()
+    finally:
+        B.rosaq_tune("splitk", 0)
+
+
+def test_strided_x_and_y():
+    from paper_2506_13472_amd import torch_glue as T
+    print("case strided", flush=True)
+    lay, Q, lam = make_case(9, 20, 256, 64, 300, O.MODE_HEADWISE)
+    ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_HEADWISE)
+    p = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_HEADWISE)
+    xb = torch.zeros((20, 256 + 64), dtype=torch.float16, device="cuda")
+    xb[:, :256] = torch.from_numpy(lay["x"]).cuda()
+    yb = torch.full((20, 64 + 8), 7.0, dtype=torch.float16, device="cuda")
+    T.linear(p, xb[:, :256], yb[:, :64])
+    torch.cuda.synchronize()
+    yh = yb.cpu().numpy()
+    assert np.all(yh[:, 64:] == 7.0)                  # nothing written outside y
+    check_output(yh[:, :64], lay["x"], Q, ref)
+    p.free()
+
+
+def test_config1_attention_projection_full_size():
+    """LLaMA-7B attention projection: D=N=4096, 32 heads, M=64, K=128, INT4, head-wise PCA from
+    512 calibration rows; the launch configuration the bench times."""
+    print("case config1", flush=True)
+    lay, Q, lam = make_case(1, 64, 4096, 4096, 512, O.MODE_HEADWISE, solver="lapack")
+    ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_HEADWISE)
+    p = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_HEADWISE)
+    check_pack(p, ref)
+    y = run_gpu(p, lay["x"])
+    check_output(y, lay["x"], Q, ref)
+    p.free()

@@ -1,0 +1,108 @@
+"""Host packer of the library against the oracle: bit-exact canonical arrays (no GPU)."""
+import numpy as np
+import pytest
+
+from oracle import rosaq_oracle as O
+from paper_2506_13472_amd import binding as B
+from paper_2506_13472_amd import synth
+
+
+def _compare(p, ref):
+    got = B.rosaq_packed_export(p)
+    for k in ("salient_idx", "W_S", "codes", "scales", "zeros"):
+        a, b = got[k], ref[k]
+        if a.dtype == np.float16:
+            a, b = a.view(np.uint16), np.asarray(b, np.float16).view(np.uint16)
+        assert a.shape == b.shape, k
+        assert np.array_equal(a, b), f"{k}: {np.sum(a != b)} of {a.size} differ"
+
+
+def rounding_margin(What):
+    """Smallest distance of an fp64 rotated weight to an fp16 rounding midpoint, in
+    units of the fp64 summation error of its dot product (D * 2^-53 * |value| scale).
+    Two independent fp64 summations round to the same fp16 when this is large."""
+    a = np.abs(What).ravel()
+    a = a[a > 2.0 ** -14]
+    e = np.floor(np.log2(a))
+    ulp = 2.0 ** (e - 10)
+    frac = a / ulp - np.floor(a / ulp)
+    dist = np.abs(frac - 0.5) * ulp
+    err = What.shape[1] * 2.0 ** -53 * np.maximum(a, 1e-30) * 4
+    return float(np.min(dist / err))
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,D,K", [(40, 256, 128), (16, 128, 0), (24, 384, 384), (17, 512, 256)])
+def test_mode_none_is_unconditionally_bit_exact(bits, N, D, K):
+    lay = synth.make_layer(10 + bits, 4, D, N, 64)
+    lam = np.abs(lay["X_cal"]).mean(axis=0)          # 'Mixed' baseline key: activation magnitude
+    ref = O.pack(lay["W"], None, lam, K, bits, O.MODE_NONE)
+    p = B.rosaq_pack_weights(lay["W"], None, lam, K, bits, B.Q_NONE, host_only=True)
+    _compare(p, ref)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_full_rotation_bit_exact(bits):
+    lay = synth.make_layer(0, 4, 256, 48, 64)        # rank-deficient calibration (64 rows < D)
+    Q, lam = O.pca_full(lay["X_cal"], "jacobi")
+    Q32 = Q.astype(np.float32)
+    ref = O.pack(lay["W"], Q32, lam, 128, bits, O.MODE_FULL)
+    assert rounding_margin(ref["What"]) > 1e3
+    p = B.rosaq_pack_weights(lay["W"], Q32, lam, 128, bits, B.Q_FULL, host_only=True)
+    _compare(p, ref)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_headwise_rotation_bit_exact(bits):
+    lay = synth.make_layer(1, 4, 512, 40, 512)
+    Qb, lam = O.pca_headwise(lay["X_cal"], 128, "jacobi")
+    Qb32 = Qb.astype(np.float32)
+    ref = O.pack(lay["W"], Qb32, lam, 128, bits, O.MODE_HEADWISE)
+    assert rounding_margin(ref["What"]) > 1e3
+    p = B.rosaq_pack_weights(lay["W"], Qb32, lam, 128, bits, B.Q_HEADWISE, host_only=True)
+    _compare(p, ref)
+    # global top-K over all heads: a prefix of each head
+    sal = B.rosaq_packed_export(p)["salient_idx"]
+    for h in range(4):
+        loc = sal[(sal >= 128 * h) & (sal < 128 * (h + 1))] - 128 * h
+        assert loc.tolist() == list(range(len(loc)))
+
+
+def test_strided_weight_and_unsorted_eigenvalues():
+    rng = np.random.default_rng(3)
+    N, D = 20, 256
+    big = (rng.standard_normal((N, D + 40)) * 0.03).astype(np.float16)
+    lam = rng.random(D)
+    lam[10] = lam[200] = lam.max()                   # a tie at the top
+    ref = O.pack(big[:, :D], None, lam, 64 + 64, 4, O.MODE_NONE)
+    p = B.rosaq_pack_weights(big, None, lam, 128, 4, B.Q_NONE, host_only=True, ldw=D + 40,
+                             out_features=N, in_features=D)
+    _compare(p, ref)
+
+
+def test_degenerate_groups_match():
+    W = np.zeros((16, 256), np.float16)
+    W[1, 128:] = 0.25                                 # constant group
+    W[2, 128:] = np.linspace(-2, -1, 128)             # all negative
+    W[3, 130] = 6e-5                                  # tiny range, fp16 subnormal scale territory
+    lam = np.arange(256, 0, -1.0)
+    for bits in (3, 4):
+        ref = O.pack(W, None, lam, 128, bits, O.MODE_NONE)
+        p = B.rosaq_pack_weights(W, None, lam, 128, bits, B.Q_NONE, host_only=True)
+        _compare(p, ref)
+
+
+def test_f16_conversion_of_rotated_weights_covers_subnormals_and_ties():
+    # Q = c * I scales W by a constant: exercises the library's fp64 -> fp16 rounding on every
+    # fp16 input value, including results that land on ties and in the subnormal range
+    D = 128
+    allh = np.arange(0, 0x7c00, dtype=np.uint16).view(np.float16)         # all finite positives
+    n = (allh.size + D - 1) // D
+    W = np.zeros(n * D, np.float16); W[:allh.size] = allh
+    W = W.reshape(n, D); W[1::2] *= np.float16(-1)
+    lam = np.arange(D, 0, -1.0)
+    for c in (np.float32(1.0) / 3, np.float32(2.0 ** -11) * 3, np.float32(0.75), np.float32(2.0 ** -12)):
+        Q = (np.eye(D) * c).astype(np.float32)
+        ref = O.pack(W, Q, lam, D, 4, O.MODE_FULL)
+        p = B.rosaq_pack_weights(W, Q, lam, D, 4, B.Q_FULL, host_only=True)
+        _compare(p, ref)
