@@ -90,7 +90,7 @@ size_t rosaq_workspace_bytes(const rosaq_packed_t* p, int32_t M);
  *     y = xhat[:, salient_idx] W_S^T + xhat[:, rest] ((q - z) s)^T
  * fp32 accumulation, y rounded to fp16 (RNE).
  *   x_dev  DEVICE fp16 [M x D], row m at x + m*ldx (ldx >= D, ldx % 8 == 0, 16-byte aligned base)
- *   y_dev  DEVICE fp16 [M x N], row m at y + m*ldy (ldy >= N, ldy % 8 == 0, 16-byte aligned base)
+ *   y_dev  DEVICE fp16 [M x N], row m at y + m*ldy (ldy >= N; any fp16-aligned base and ldy)
  *   ws_dev DEVICE scratch of at least rosaq_workspace_bytes(p, M), 256-byte aligned;
  *          contents need not be preserved or initialised between calls
  * Asynchronous on hip_stream; allocates nothing and never synchronises.  Calls on
@@ -121,8 +121,10 @@ int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* 
 int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t* W_S,
                         uint8_t* codes, uint16_t* scales, uint16_t* zeros);
 
-/* Tuning aid for benchmarks: key "splitk" (0 = heuristic) or "wpb" override the
- * launch heuristics of later rosaq_linear* calls in this process. */
+/* Tuning aid for benchmarks; affects later rosaq_linear* calls in this process.
+ *   "splitk"  split-K factor (0 = heuristic)      "wpb"  waves per workgroup (0, 4, 8)
+ *   "stages"  3 = whole call (default), 1 = prologue kernels only, 2 = main GEMM only
+ *             (2 reuses the rotated activations a previous call left in the workspace) */
 int rosaq_tune(const char* key, int32_t value);
 
 void rosaq_free(rosaq_packed_t* p);

@@ -96,6 +96,7 @@ def jacobi_eigh(C, tol: float = 1e-13, max_sweeps: int = 100):
     if n == 1 or normA == 0.0:
         return np.diag(A).copy(), V
     rounds = list(_round_robin_pairs(n))
+    tiny = np.finfo(np.float64).eps * normA / n
     for _ in range(max_sweeps):
         off = np.linalg.norm(A - np.diag(np.diag(A)))
         if off <= tol * normA:
@@ -104,10 +105,14 @@ def jacobi_eigh(C, tol: float = 1e-13, max_sweeps: int = 100):
             apq = A[p, q]
             app = A[p, p]
             aqq = A[q, q]
-            # rotation angle: tan(2 theta) = 2 a_pq / (a_qq - a_pp)
-            act = np.abs(apq) > 1e-300
+            # entries already at round-off level are set to zero without a rotation
+            small = np.abs(apq) <= tiny
+            A[p[small], q[small]] = 0.0
+            A[q[small], p[small]] = 0.0
+            act = ~small
+            # rotation angle: tan(2 theta) = 2 a_pq / (a_qq - a_pp); t = tan(theta), smaller root
             tau = np.where(act, (aqq - app) / (2.0 * np.where(act, apq, 1.0)), 0.0)
-            t = np.where(act, np.sign(tau) / (np.abs(tau) + np.sqrt(1.0 + tau * tau)), 0.0)
+            t = np.where(act, np.sign(tau) / (np.abs(tau) + np.hypot(1.0, tau)), 0.0)
             t = np.where(act & (tau == 0.0), 1.0, t)
             c = 1.0 / np.sqrt(1.0 + t * t)
             s = t * c

@@ -48,6 +48,12 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2506_13472_amd.build`")
+        try:
+            # PyTorch ships its own HIP runtime (same soname); load it first so the
+            # process holds one runtime and streams / pointers are interchangeable.
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
         L.rosaq_pack_weights.argtypes = [C.POINTER(PackDesc), vp, C.POINTER(vp)]

@@ -15,6 +15,7 @@ void set_error(const std::string& s) { g_error = s; }
 
 static int g_tune_splitk = 0;  // 0 = heuristic
 static int g_tune_wpb = 0;     // 0 = default (4 waves per workgroup)
+static int g_tune_stages = 3;  // bit 0: prologue kernels, bit 1: main GEMM (timing aid)
 
 static int fail(int code, const std::string& msg) {
   set_error(msg);
@@ -142,8 +143,9 @@ static int check_call(const rosaq_packed_t* p, const void* x, int32_t M, int64_t
   if (M < 1) return fail(ROSAQ_ERR_SHAPE, "M must be at least 1");
   if (M > kMaxMBlocks * kMBlock) return fail(ROSAQ_ERR_SHAPE, "M above 4096: split the call");
   if (ldx < p->c.D || ldy < p->c.N) return fail(ROSAQ_ERR_SHAPE, "leading dimension smaller than width");
-  if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16 || ldx % 8 || ldy % 8)
-    return fail(ROSAQ_ERR_ALIGN, "x, y must be 16-byte aligned and ldx, ldy multiples of 8");
+  if (reinterpret_cast<uintptr_t>(x) % 16 || ldx % 8)
+    return fail(ROSAQ_ERR_ALIGN, "x must be 16-byte aligned and ldx a multiple of 8");
+  if (reinterpret_cast<uintptr_t>(y) % 2) return fail(ROSAQ_ERR_ALIGN, "y must be 2-byte aligned");
   *plan = plan_workspace(*p, M);
   if (!ws || ws_bytes < plan->total) return fail(ROSAQ_ERR_WORKSPACE, "workspace missing or too small");
   if (reinterpret_cast<uintptr_t>(ws) % 256) return fail(ROSAQ_ERR_ALIGN, "workspace must be 256-byte aligned");
@@ -204,7 +206,9 @@ int rosaq_linear(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t 
   if (rc != ROSAQ_OK) return rc;
   const Canonical& c = p->c;
   char* ws = static_cast<char*>(ws_dev);
-  if (c.q_mode == ROSAQ_Q_NONE) {
+  if (!(g_tune_stages & 1)) {
+    // timing aid: reuse the xhat fragments a previous call left in the workspace
+  } else if (c.q_mode == ROSAQ_Q_NONE) {
     rc = launch_gather(x_dev, ldx, M, c.D, p->d_perm, ws + w.xf_a, hip_stream);
     if (rc != ROSAQ_OK) return rc;
   } else {
@@ -223,6 +227,7 @@ int rosaq_linear(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t 
     rc = launch_gemm(a, g_tune_wpb, hip_stream);
     if (rc != ROSAQ_OK) return rc;
   }
+  if (!(g_tune_stages & 2)) return ROSAQ_OK;
   return run_main_gemm(p, w, M, y_dev, ldy, ws, hip_stream);
 }
 
@@ -233,8 +238,11 @@ int rosaq_linear_headwise(const rosaq_packed_t* p, const void* x_dev, int32_t M,
   int rc = check_call(p, x_dev, M, ldx, y_dev, ldy, ws_dev, ws_bytes, true, &w);
   if (rc != ROSAQ_OK) return rc;
   char* ws = static_cast<char*>(ws_dev);
-  rc = launch_rotate_headwise(x_dev, ldx, M, p->c.D, p->d_qf, p->d_pos, ws + w.xf_a, hip_stream);
-  if (rc != ROSAQ_OK) return rc;
+  if (g_tune_stages & 1) {
+    rc = launch_rotate_headwise(x_dev, ldx, M, p->c.D, p->d_qf, p->d_pos, ws + w.xf_a, hip_stream);
+    if (rc != ROSAQ_OK) return rc;
+  }
+  if (!(g_tune_stages & 2)) return ROSAQ_OK;
   return run_main_gemm(p, w, M, y_dev, ldy, ws, hip_stream);
 }
 
@@ -269,6 +277,10 @@ int rosaq_tune(const char* key, int32_t value) {
   if (!std::strcmp(key, "wpb")) {
     if (value != 0 && value != 4 && value != 8) return fail(ROSAQ_ERR_ARG, "wpb must be 0, 4 or 8");
     g_tune_wpb = value; return ROSAQ_OK;
+  }
+  if (!std::strcmp(key, "stages")) {
+    if (value < 1 || value > 3) return fail(ROSAQ_ERR_ARG, "stages must be 1, 2 or 3");
+    g_tune_stages = value; return ROSAQ_OK;
   }
   return fail(ROSAQ_ERR_ARG, "unknown tuning key");
 }

@@ -43,7 +43,15 @@ def check_pack(p, ref):
         assert np.array_equal(a, b), k
 
 
-def make_case(seed, M, D, N, n_cal, mode, solver="jacobi"):
+import functools
+
+
+@functools.lru_cache(maxsize=4)
+def make_case(seed, M, D, N, n_cal, mode, solver=None):
+    """Inputs + rotation.  The oracle's Jacobi solver serves the 128-blocks and D <= 256;
+    larger dense cases use its LAPACK route (checked against Jacobi in the CPU tests)."""
+    if solver is None:
+        solver = "jacobi" if (mode == O.MODE_HEADWISE or D <= 256) else "lapack"
     lay = synth.make_layer(seed, M, D, N, n_cal)
     if mode == O.MODE_NONE:
         Q, lam = None, np.abs(lay["X_cal"]).mean(axis=0)
