@@ -84,8 +84,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of one hipGraph per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16", action="store_true", help="skip the fp16 GEMM comparison")
-    ap.add_argument("--splitk", type=int, default=0, help="tuning aid: force the split-K factor")
-    ap.add_argument("--wpb", type=int, default=0, help="tuning aid: waves per workgroup (4 or 8)")
+    ap.add_argument("--mt", type=int, default=0, help="tuning aid: 16-row tiles per workgroup")
+    ap.add_argument("--nt", type=int, default=0, help="tuning aid: 16-channel tiles per workgroup")
+    ap.add_argument("--wpb", type=int, default=0, help="tuning aid: waves per workgroup (8 or 16)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
@@ -98,8 +99,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     B.lib()
-    B.rosaq_tune("splitk", args.splitk)
-    B.rosaq_tune("wpb", args.wpb)
+    for key in ("mt", "nt", "wpb"):
+        B.rosaq_tune(key, getattr(args, key))
 
     # ---- synthetic layers, packed through the C ABI --------------------------------
     t_pack = time.perf_counter()
@@ -206,7 +207,7 @@ def main():
                    "bits": BITS, "group": GROUP, "heads": HEADS, "calls_per_step": CALLS_PER_STEP,
                    "distinct_packed_weights": len(handles), "packed_MB": round(packed_bytes / 1e6, 1),
                    "launch": "eager" if args.no_graph else "hipGraph per step",
-                   "splitk": args.splitk or "heuristic", "wpb": args.wpb or 4},
+                   "tiles": {k: getattr(args, k) or "heuristic" for k in ("mt", "nt", "wpb")}},
         "us_per_call": round(us_call, 3),
         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         "tflops": round(2.0 * M * N * (D + 128) / (us_call * 1e-6) / 1e12, 2),
@@ -214,7 +215,7 @@ def main():
         "rotation_kernel_us": round(ev_rot / n_calls * 1e6, 3),
         "pack_seconds_per_layer": round(t_pack / len(handles), 3),
         "fp16_gemm": fp16,
-        "roofline": {"kernel": "gemm_kernel<4,4,4,4>", "bound": "hbm", "achieved": round(gemm_gbs, 1),
+        "roofline": {"kernel": "gemm_kernel", "bound": "hbm", "achieved": round(gemm_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
                      "traffic": None, "bytes_per_launch": ab["gemm_kernel"],
                      "us_per_launch": round(us_gemm, 3)},

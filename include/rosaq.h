@@ -93,8 +93,8 @@ size_t rosaq_workspace_bytes(const rosaq_packed_t* p, int32_t M);
  *   y_dev  DEVICE fp16 [M x N], row m at y + m*ldy (ldy >= N; any fp16-aligned base and ldy)
  *   ws_dev DEVICE scratch of at least rosaq_workspace_bytes(p, M), 256-byte aligned;
  *          contents need not be preserved or initialised between calls
- * Asynchronous on hip_stream; allocates nothing and never synchronises.  Calls on
- * the same handle must not overlap in time (they share split-K counters).
+ * Asynchronous on hip_stream; allocates nothing and never synchronises.  Calls that
+ * share a workspace must not overlap in time.
  * Errors: NULL, SHAPE, MODE (HEADWISE handle), ALIGN, WORKSPACE, HOSTONLY, HIP. */
 int rosaq_linear(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t ldx,
                  void* y_dev, int64_t ldy, void* ws_dev, size_t ws_bytes, void* hip_stream);
@@ -122,7 +122,8 @@ int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t*
                         uint8_t* codes, uint16_t* scales, uint16_t* zeros);
 
 /* Tuning aid for benchmarks; affects later rosaq_linear* calls in this process.
- *   "splitk"  split-K factor (0 = heuristic)      "wpb"  waves per workgroup (0, 4, 8)
+ *   "mt", "nt"  16-row / 16-channel MFMA tiles per workgroup (0 = heuristic, 1, 2, 4)
+ *   "wpb"     waves per workgroup splitting the contraction (0 = default, 8, 16)
  *   "stages"  3 = whole call (default), 1 = prologue kernels only, 2 = main GEMM only
  *             (2 reuses the rotated activations a previous call left in the workspace) */
 int rosaq_tune(const char* key, int32_t value);

@@ -13,8 +13,7 @@ namespace rosaq {
 static thread_local std::string g_error;
 void set_error(const std::string& s) { g_error = s; }
 
-static int g_tune_splitk = 0;  // 0 = heuristic
-static int g_tune_wpb = 0;     // 0 = default (4 waves per workgroup)
+static GemmTune g_tune;         // all zero = heuristics
 static int g_tune_stages = 3;  // bit 0: prologue kernels, bit 1: main GEMM (timing aid)
 
 static int fail(int code, const std::string& msg) {
@@ -26,15 +25,9 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 static int padded_tiles(int n) { return ((n + 127) / 128) * 8; }  // 16-channel tiles, whole 128s
 
-static int splits_for(int M, int N, int units) {
-  int s = g_tune_splitk > 0 ? g_tune_splitk : pick_splits(M, N, units);
-  return std::max(1, std::min(s, std::max(1, units)));
-}
-
 // Workspace carve-up for one call with M rows.
 struct WsPlan {
-  size_t xf_a = 0, xf_b = 0, part_main = 0, part_rot = 0, total = 0;
-  int s_main = 1, s_rot = 1;
+  size_t xf_a = 0, xf_b = 0, total = 0;
 };
 
 static WsPlan plan_workspace(const rosaq_packed& p, int M) {
@@ -42,19 +35,11 @@ static WsPlan plan_workspace(const rosaq_packed& p, int M) {
   const Canonical& c = p.c;
   const size_t mblocks = (static_cast<size_t>(M) + kMBlock - 1) / kMBlock;
   const size_t xf_bytes = mblocks * (c.D / kKStep) * 4 * 64 * 16;
-  const size_t tile_bytes = 4 * 4 * 64 * 16;  // one 64 x 64 fp32 tile
-  w.s_main = splits_for(M, c.N, c.K / kKStep + c.G);
   size_t off = 0;
   w.xf_a = off; off += align_up(xf_bytes, 256);
   if (c.q_mode == ROSAQ_Q_FULL) {
     w.xf_b = off; off += align_up(xf_bytes, 256);
-    w.s_rot = splits_for(M, c.D, c.D / kKStep);
   }
-  w.part_main = off;
-  if (w.s_main > 1) off += mblocks * (padded_tiles(c.N) / 4) * w.s_main * tile_bytes;
-  w.part_rot = off;
-  if (c.q_mode == ROSAQ_Q_FULL && w.s_rot > 1)
-    off += mblocks * (padded_tiles(c.D) / 4) * w.s_rot * tile_bytes;
   w.total = off;
   return w;
 }
@@ -97,11 +82,7 @@ static int upload(rosaq_packed* p, const float* Q, hipStream_t st) {
     build_device_image(p->c, Q, &img);
   } catch (const std::bad_alloc&) { return fail(ROSAQ_ERR_NOMEM, "out of host memory"); }
   const Canonical& c = p->c;
-  const size_t n_cnt_main = static_cast<size_t>(kMaxMBlocks) * (padded_tiles(c.N) / 4);
-  const size_t n_cnt_rot = static_cast<size_t>(kMaxMBlocks) * (padded_tiles(c.D) / 4);
-  p->counters_per_set = n_cnt_main;
   struct Part { const void* src; size_t bytes; void** dst; };
-  void* d_cnt = nullptr;
   void* d_perm = nullptr;
   void* d_pos = nullptr;
   Part parts[] = {
@@ -111,7 +92,6 @@ static int upload(rosaq_packed* p, const float* Q, hipStream_t st) {
       {img.qf.data(), img.qf.size() * 4, &p->d_qf},
       {c.perm.data(), c.perm.size() * 4, &d_perm},
       {c.pos.data(), c.pos.size() * 4, &d_pos},
-      {nullptr, (n_cnt_main + n_cnt_rot) * 4, &d_cnt},
   };
   size_t total = 0;
   for (const Part& q : parts) total += align_up(std::max<size_t>(q.bytes, 16), 256);
@@ -122,13 +102,11 @@ static int upload(rosaq_packed* p, const float* Q, hipStream_t st) {
   for (const Part& q : parts) {
     *q.dst = static_cast<char*>(p->d_blob) + off;
     if (q.src && q.bytes) ROSAQ_HIP(hipMemcpyAsync(*q.dst, q.src, q.bytes, hipMemcpyHostToDevice, st));
-    else if (q.bytes) ROSAQ_HIP(hipMemsetAsync(*q.dst, 0, q.bytes, st));
     off += align_up(std::max<size_t>(q.bytes, 16), 256);
   }
   ROSAQ_HIP(hipStreamSynchronize(st));   // staging vectors die with this frame
   p->d_perm = static_cast<int32_t*>(d_perm);
   p->d_pos = static_cast<int32_t*>(d_pos);
-  p->d_counters = static_cast<uint32_t*>(d_cnt);
   p->host_only = false;
   return ROSAQ_OK;
 }
@@ -141,7 +119,7 @@ static int check_call(const rosaq_packed_t* p, const void* x, int32_t M, int64_t
     return fail(ROSAQ_ERR_MODE, headwise ? "rosaq_linear_headwise needs a HEADWISE handle"
                                          : "rosaq_linear does not serve a HEADWISE handle");
   if (M < 1) return fail(ROSAQ_ERR_SHAPE, "M must be at least 1");
-  if (M > kMaxMBlocks * kMBlock) return fail(ROSAQ_ERR_SHAPE, "M above 4096: split the call");
+  if (M > (1 << 20)) return fail(ROSAQ_ERR_SHAPE, "M above 2^20: split the call");
   if (ldx < p->c.D || ldy < p->c.N) return fail(ROSAQ_ERR_SHAPE, "leading dimension smaller than width");
   if (reinterpret_cast<uintptr_t>(x) % 16 || ldx % 8)
     return fail(ROSAQ_ERR_ALIGN, "x must be 16-byte aligned and ldx a multiple of 8");
@@ -159,13 +137,11 @@ static int run_main_gemm(const rosaq_packed_t* p, const WsPlan& w, int M, void* 
   GemmArgs a{};
   a.xf = ws + (c.q_mode == ROSAQ_Q_FULL ? w.xf_b : w.xf_a);
   a.wS = p->d_wS; a.wq = p->d_wq; a.sz = p->d_sz;
-  a.partial = reinterpret_cast<float*>(ws + w.part_main);
-  a.counters = p->d_counters;
   a.out = y; a.ldo = ldy; a.M = M; a.N = c.N;
   a.ntiles = padded_tiles(c.N);
   a.ks_s = c.K / kKStep; a.G = c.G; a.KS = c.D / kKStep; a.KS_out = 0;
-  a.bits = c.bits; a.splits = w.s_main; a.out_frag = 0;
-  return launch_gemm(a, g_tune_wpb, stream);
+  a.bits = c.bits; a.out_frag = 0;
+  return launch_gemm(a, g_tune, stream);
 }
 
 }  // namespace rosaq
@@ -218,13 +194,11 @@ int rosaq_linear(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t 
     if (rc != ROSAQ_OK) return rc;
     GemmArgs a{};
     a.xf = ws + w.xf_a; a.wS = p->d_qf; a.wq = nullptr; a.sz = nullptr;
-    a.partial = reinterpret_cast<float*>(ws + w.part_rot);
-    a.counters = p->d_counters + p->counters_per_set;
     a.out = ws + w.xf_b; a.ldo = 0; a.M = M; a.N = c.D;
     a.ntiles = padded_tiles(c.D);
     a.ks_s = c.D / kKStep; a.G = 0; a.KS = c.D / kKStep; a.KS_out = c.D / kKStep;
-    a.bits = 4; a.splits = w.s_rot; a.out_frag = 1;
-    rc = launch_gemm(a, g_tune_wpb, hip_stream);
+    a.bits = 4; a.out_frag = 1;
+    rc = launch_gemm(a, g_tune, hip_stream);
     if (rc != ROSAQ_OK) return rc;
   }
   if (!(g_tune_stages & 2)) return ROSAQ_OK;
@@ -273,10 +247,14 @@ int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t*
 
 int rosaq_tune(const char* key, int32_t value) {
   if (!key) return fail(ROSAQ_ERR_NULL, "key is NULL");
-  if (!std::strcmp(key, "splitk")) { g_tune_splitk = value; return ROSAQ_OK; }
   if (!std::strcmp(key, "wpb")) {
-    if (value != 0 && value != 4 && value != 8) return fail(ROSAQ_ERR_ARG, "wpb must be 0, 4 or 8");
-    g_tune_wpb = value; return ROSAQ_OK;
+    if (value != 0 && value != 8 && value != 16) return fail(ROSAQ_ERR_ARG, "wpb must be 0, 8 or 16");
+    g_tune.wpb = value; return ROSAQ_OK;
+  }
+  if (!std::strcmp(key, "mt") || !std::strcmp(key, "nt")) {
+    if (value != 0 && value != 1 && value != 2 && value != 4)
+      return fail(ROSAQ_ERR_ARG, "tile counts must be 0, 1, 2 or 4");
+    (key[0] == 'm' ? g_tune.mt : g_tune.nt) = value; return ROSAQ_OK;
   }
   if (!std::strcmp(key, "stages")) {
     if (value < 1 || value > 3) return fail(ROSAQ_ERR_ARG, "stages must be 1, 2 or 3");

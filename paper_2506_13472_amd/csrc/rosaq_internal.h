@@ -14,7 +14,6 @@ constexpr int kHeadDim = 128;  // block size of the head-wise rotation (Eq. 6)
 constexpr int kKStep = 32;     // contraction depth of one v_mfma_f32_16x16x32_f16
 constexpr int kTileN = 16;     // output channels per MFMA tile
 constexpr int kMBlock = 64;    // rows of x handled by one workgroup pass (4 MFMA row tiles)
-constexpr int kMaxMBlocks = 64;  // split-K counters are provisioned for M <= 4096
 
 // ---- fp16 <-> fp64 on the host (rosaq_pack.cpp) -------------------------------
 uint16_t f64_to_f16(double v);  // round-half-to-even, one rounding, overflow -> inf
@@ -51,26 +50,25 @@ struct GemmArgs {
   const void* wS;        // fp16 fragments  [ntiles][ks_s][64]   x 16 B
   const void* wq;        // low-bit fragments
   const void* sz;        // scale/zero pairs
-  float* partial;        // split-K partial tiles
-  uint32_t* counters;    // one per (mblock, channel chunk), zero between calls
   void* out;             // y (row-major fp16) or xhat fragments
   int64_t ldo;           // leading dimension of y
   int M, N;              // valid rows / output channels
-  int ntiles;            // ceil(N / 16)
+  int ntiles;            // 16-channel tiles in the weight image (multiple of 8)
   int ks_s;              // fp16 k-steps (K/32)
   int G;                 // low-bit groups
   int KS;                // k-steps of the xf operand (D/32)
   int KS_out;            // k-steps of the output when out is in fragment order
   int bits;              // 3 or 4 (ignored when G == 0)
-  int splits;            // split-K factor S
   int out_frag;          // 0: y row-major, 1: xhat fragment order
 };
-int launch_gemm(const GemmArgs& a, int wpb_override, void* stream);
+struct GemmTune { int mt = 0, nt = 0, wpb = 0; };   // 0 = heuristic
+struct GemmShape { int mt, nt, wpb; };
+GemmShape pick_gemm_shape(int M, int ntiles, const GemmTune& tune);
+int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream);
 int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_dev,
                   void* xf, void* stream);
 int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void* qh,
                            const int32_t* pos_dev, void* xf, void* stream);
-int pick_splits(int M, int N, int units);
 
 void set_error(const std::string& s);
 
@@ -89,6 +87,4 @@ struct rosaq_packed {
   void* d_qf = nullptr;
   int32_t* d_perm = nullptr;
   int32_t* d_pos = nullptr;
-  uint32_t* d_counters = nullptr;   // two sets: rotation GEMM and main GEMM
-  size_t counters_per_set = 0;
 };

@@ -61,15 +61,14 @@ struct GemmDev {
   const uint4* wS;
   const uint32_t* wq;
   const uint32_t* sz;
-  float4* partial;
-  uint32_t* counters;
   _Float16* out;
   int64_t ldo;
-  int M, N, ks_s, G, KS, KS_out, splits, out_frag, chunks, units;
+  int M, N, ks_s, G, KS, KS_out, out_frag, chunks, mgroups;
 };
 
-// Store one accumulator fragment: lane holds rows 4*(lane/16)+i, column lane%16.
-__device__ __forceinline__ void store_fragment(const GemmDev& p, float4 v, int mb, int mt, int tile,
+// Store one accumulator fragment of row tile `mtile` (16 rows) and channel tile
+// `tile`: lane holds rows 4*(lane/16)+i, column lane%16.
+__device__ __forceinline__ void store_fragment(const GemmDev& p, float4 v, int mtile, int tile,
                                                int lane) {
   const int n = tile * kTileN + (lane & 15);
   if (n >= p.N) return;
@@ -77,7 +76,7 @@ __device__ __forceinline__ void store_fragment(const GemmDev& p, float4 v, int m
   if (!p.out_frag) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int m = mb * kMBlock + mt * 16 + 4 * (lane >> 4) + i;
+      const int m = mtile * 16 + 4 * (lane >> 4) + i;
       if (m < p.M) p.out[static_cast<int64_t>(m) * p.ldo + n] = static_cast<_Float16>(vv[i]);
     }
   } else {
@@ -86,36 +85,32 @@ __device__ __forceinline__ void store_fragment(const GemmDev& p, float4 v, int m
     for (int i = 0; i < 4; ++i) {
       const int lane2 = 4 * (lane >> 4) + i + 16 * j;
       const size_t off =
-          (((static_cast<size_t>(mb) * p.KS_out + ks) * 4 + mt) * 64 + lane2) * 8 + e;
+          (((static_cast<size_t>(mtile >> 2) * p.KS_out + ks) * 4 + (mtile & 3)) * 64 + lane2) * 8 + e;
       p.out[off] = static_cast<_Float16>(vv[i]);
     }
   }
 }
 
-// y tile [64 x NT*16] for a range of contraction "units": the first ks_s units are
-// fp16 k-steps (32 channels each, the salient group of Eq. 3), the next G units
-// are low-bit groups (128 channels each).  A workgroup owns one channel chunk and
-// one split of the unit range; its waves take units round-robin, accumulate in
-// fp32 registers, and are summed through LDS in a fixed order.  With splits > 1
-// workgroups park their tile in `partial` and the last one to arrive adds the
-// tiles in split order, so the result does not depend on scheduling.
+// One workgroup computes a [MT*16 rows] x [NT*16 channels] tile of the output over
+// the whole contraction.  The contraction is cut into "units": first ks_s fp16
+// k-steps of 32 channels (the salient group of Eq. 3), then G low-bit groups of 128
+// channels.  The WPB waves take units round-robin (split-K inside the workgroup),
+// each streaming its weight fragments from HBM straight into registers, and are
+// summed through LDS in wave order, so the result does not depend on scheduling.
+// Workgroups that share a channel chunk (different row tiles) are placed on one XCD
+// so that the weights are fetched from HBM once and found in that XCD's L2 after.
 template <int BITS, int MT, int NT, int WPB>
 __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
   __shared__ float4 red[WPB][NT * MT][64];
-  __shared__ int s_last;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int mb = blockIdx.y;
-  // Workgroups go to the 8 XCDs round-robin by linear id: keep all splits of one
-  // channel chunk on one XCD so their partial tiles meet in that XCD's L2.
   const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int chunk = xcd + 8 * (local / p.splits);
-  const int split = local % p.splits;
+  const int chunk = xcd + 8 * (local / p.mgroups);
+  const int mg = local % p.mgroups;
   if (chunk >= p.chunks) return;
   const int tile0 = chunk * NT;
-  const int u0 = static_cast<int>(static_cast<int64_t>(p.units) * split / p.splits);
-  const int u1 = static_cast<int>(static_cast<int64_t>(p.units) * (split + 1) / p.splits);
+  const int mtile0 = mg * MT;
 
   floatx4 acc[NT][MT];
 #pragma unroll
@@ -123,72 +118,91 @@ __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  const uint4* xf = p.xf + static_cast<size_t>(mb) * p.KS * 4 * 64 + lane;
+  // xhat fragment of row tile mtile0+mt and k-step ks: xa[mt][ks * 256]
+  const uint4* xa[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int mtile = mtile0 + mt;
+    xa[mt] = p.xf + (static_cast<size_t>(mtile >> 2) * p.KS * 4 + (mtile & 3)) * 64 + lane;
+  }
 
-  for (int u = u0 + wave; u < u1; u += WPB) {
-    if (u < p.ks_s) {
-      half8 a[MT];
+  // ---- fp16 units --------------------------------------------------------------
+  for (int u = wave; u < p.ks_s; u += WPB) {
+    half8 a[MT];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) a[mt] = as_h8(xf[(static_cast<size_t>(u) * 4 + mt) * 64]);
+    for (int mt = 0; mt < MT; ++mt) a[mt] = as_h8(xa[mt][static_cast<size_t>(u) * 256]);
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const half8 b = as_h8(p.wS[(static_cast<size_t>(tile0 + nt) * p.ks_s + u) * 64 + lane]);
+    for (int nt = 0; nt < NT; ++nt) {
+      const half8 b = as_h8(p.wS[(static_cast<size_t>(tile0 + nt) * p.ks_s + u) * 64 + lane]);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = mfma16(a[mt], b, acc[nt][mt]);
-      }
-    } else {
-      const int g = u - p.ks_s;
-      const int ks0 = p.ks_s + 4 * g;
-      // issue the weight loads first: they are the HBM stream
-      uint32_t cw[NT][4];
-      uint32_t szv[NT];
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const size_t fi = (static_cast<size_t>(tile0 + nt) * p.G + g) * 64 + lane;
-        if (BITS == 4) {
-          const uint4 c = reinterpret_cast<const uint4*>(p.wq)[fi];
-          cw[nt][0] = c.x; cw[nt][1] = c.y; cw[nt][2] = c.z; cw[nt][3] = c.w;
-        } else {
-          cw[nt][0] = p.wq[fi * 3 + 0];
-          cw[nt][1] = p.wq[fi * 3 + 1];
-          cw[nt][2] = p.wq[fi * 3 + 2];
-          cw[nt][3] = 0;
-        }
-        szv[nt] = p.sz[(static_cast<size_t>(tile0 + nt) * p.G + g) * 16 + (lane & 15)];
-      }
-      half8 a[4][MT];
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          a[t][mt] = as_h8(xf[(static_cast<size_t>(ks0 + t) * 4 + mt) * 64]);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const half2v sz2 = as_h2(szv[nt]);
-        const float s = static_cast<float>(sz2.x);
-        const _Float16 z = sz2.y;
-        const _Float16 clo = -(z + (_Float16)1024.0f);
-        const _Float16 chi = -(z + (_Float16)64.0f);
-        const half2v c_lo = {clo, clo}, c_hi = {chi, chi};
-        floatx4 tmp[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) tmp[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          half8 b;
-          if (BITS == 4) b = dequant4(cw[nt][t], c_lo, c_hi);
-          else b = dequant3(cw[nt][t >> 1], cw[nt][2], t, c_lo);
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) tmp[mt] = mfma16(a[t][mt], b, tmp[mt]);
-        }
-        // the group scale is applied once per 128 channels, in fp32
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[nt][mt] += s * tmp[mt];
-      }
+      for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = mfma16(a[mt], b, acc[nt][mt]);
     }
   }
 
-  // ---- reduce the waves of this workgroup through LDS, fixed order ----------------
+  // ---- low-bit units, two in flight per wave -----------------------------------------
+  struct GroupRegs {
+    uint32_t cw[NT][4];
+    uint32_t sz[NT];
+    uint4 a[4][MT];
+  };
+  auto load_group = [&](int g, GroupRegs& r) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const size_t fi = (static_cast<size_t>(tile0 + nt) * p.G + g) * 64 + lane;
+      if (BITS == 4) {
+        const uint4 c = reinterpret_cast<const uint4*>(p.wq)[fi];
+        r.cw[nt][0] = c.x; r.cw[nt][1] = c.y; r.cw[nt][2] = c.z; r.cw[nt][3] = c.w;
+      } else {
+        r.cw[nt][0] = p.wq[fi * 3 + 0];
+        r.cw[nt][1] = p.wq[fi * 3 + 1];
+        r.cw[nt][2] = p.wq[fi * 3 + 2];
+        r.cw[nt][3] = 0;
+      }
+      r.sz[nt] = p.sz[(static_cast<size_t>(tile0 + nt) * p.G + g) * 16 + (lane & 15)];
+    }
+    const size_t ks0 = static_cast<size_t>(p.ks_s + 4 * g);
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) r.a[t][mt] = xa[mt][(ks0 + t) * 256];
+  };
+  auto compute_group = [&](const GroupRegs& r) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const half2v sz2 = as_h2(r.sz[nt]);
+      const float s = static_cast<float>(sz2.x);
+      const _Float16 z = sz2.y;
+      const _Float16 clo = -(z + (_Float16)1024.0f);
+      const _Float16 chi = -(z + (_Float16)64.0f);
+      const half2v c_lo = {clo, clo}, c_hi = {chi, chi};
+      floatx4 tmp[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) tmp[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        half8 b;
+        if (BITS == 4) b = dequant4(r.cw[nt][t], c_lo, c_hi);
+        else b = dequant3(r.cw[nt][t >> 1], r.cw[nt][2], t, c_lo);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) tmp[mt] = mfma16(as_h8(r.a[t][mt]), b, tmp[mt]);
+      }
+      // the group scale is applied once per 128 channels, in fp32
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) acc[nt][mt] += s * tmp[mt];
+    }
+  };
+  // unit u = ks_s + g belongs to wave u % WPB
+  const int g_first = (wave + WPB - p.ks_s % WPB) % WPB;
+  for (int g = g_first; g < p.G; g += 2 * WPB) {
+    GroupRegs r0, r1;
+    load_group(g, r0);
+    const bool two = g + WPB < p.G;
+    if (two) load_group(g + WPB, r1);
+    compute_group(r0);
+    if (two) compute_group(r1);
+  }
+
+  // ---- sum the waves of this workgroup through LDS in wave order -----------------------
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -198,63 +212,16 @@ __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
     }
   __syncthreads();
 
-  constexpr int kSlots = NT * MT;           // accumulator fragments per tile
-  constexpr int kPerWave = (kSlots + WPB - 1) / WPB;
-  float4 sum[kPerWave];
+  constexpr int kSlots = NT * MT;
+  for (int slot = wave; slot < kSlots; slot += WPB) {
+    float4 v = red[0][slot][lane];
 #pragma unroll
-  for (int i = 0; i < kPerWave; ++i) {
-    const int slot = wave + i * WPB;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (slot < kSlots) {
-      v = red[0][slot][lane];
-#pragma unroll
-      for (int w = 1; w < WPB; ++w) {
-        const float4 o = red[w][slot][lane];
-        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-      }
-    }
-    sum[i] = v;
-  }
-
-  if (p.splits == 1) {
-#pragma unroll
-    for (int i = 0; i < kPerWave; ++i) {
-      const int slot = wave + i * WPB;
-      if (slot < kSlots) store_fragment(p, sum[i], mb, slot % MT, tile0 + slot / MT, lane);
-    }
-    return;
-  }
-
-  // ---- split-K across workgroups: park, count, last arrival sums in split order ----
-  const size_t tile_id = static_cast<size_t>(mb) * p.chunks + chunk;
-  float4* mine = p.partial + (tile_id * p.splits + split) * (kSlots * 64);
-#pragma unroll
-  for (int i = 0; i < kPerWave; ++i) {
-    const int slot = wave + i * WPB;
-    if (slot < kSlots) mine[slot * 64 + lane] = sum[i];
-  }
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const uint32_t old = atomicAdd(&p.counters[tile_id], 1u);
-    s_last = (old == static_cast<uint32_t>(p.splits) - 1u);
-  }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  const float4* all = p.partial + tile_id * p.splits * (kSlots * 64);
-#pragma unroll
-  for (int i = 0; i < kPerWave; ++i) {
-    const int slot = wave + i * WPB;
-    if (slot >= kSlots) continue;
-    float4 v = all[slot * 64 + lane];
-    for (int s = 1; s < p.splits; ++s) {
-      const float4 o = all[(static_cast<size_t>(s) * kSlots + slot) * 64 + lane];
+    for (int w = 1; w < WPB; ++w) {
+      const float4 o = red[w][slot][lane];
       v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
     }
-    store_fragment(p, v, mb, slot % MT, tile0 + slot / MT, lane);
+    store_fragment(p, v, mtile0 + slot % MT, tile0 + slot / MT, lane);
   }
-  if (threadIdx.x == 0) p.counters[tile_id] = 0u;   // ready for the next call
 }
 
 // xhat fragments from x by a column permutation (or identity): the prologue of
@@ -325,50 +292,58 @@ static int hip_fail(hipError_t e, const char* what) {
   return ROSAQ_ERR_HIP;
 }
 
-int pick_splits(int M, int N, int units) {
-  const int ntiles = ((N + 127) / 128) * 8;
-  const int chunks = ntiles / 4;
-  const int mblocks = (M + kMBlock - 1) / kMBlock;
-  const int wgs = chunks * mblocks;
-  int s = (256 + wgs - 1) / wgs;            // aim at one workgroup per compute unit
-  s = std::min(s, std::max(1, units / 4));  // keep at least one unit per wave
-  return std::max(1, std::min(s, 64));
-}
-
-template <int BITS, int MT, int WPB>
-static int launch_gemm_t(const GemmDev& d, int mblocks, hipStream_t st) {
-  const int xblocks = ((d.chunks + 7) / 8) * 8 * d.splits;
-  hipLaunchKernelGGL((gemm_kernel<BITS, MT, 4, WPB>), dim3(xblocks, mblocks), dim3(WPB * 64), 0, st, d);
+template <int BITS, int MT, int NT, int WPB>
+static int launch_gemm_t(const GemmDev& d, hipStream_t st) {
+  const int xblocks = ((d.chunks + 7) / 8) * 8 * d.mgroups;
+  hipLaunchKernelGGL((gemm_kernel<BITS, MT, NT, WPB>), dim3(xblocks), dim3(WPB * 64), 0, st, d);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "gemm_kernel launch");
 }
 
-int launch_gemm(const GemmArgs& a, int wpb_override, void* stream) {
+GemmShape pick_gemm_shape(int M, int ntiles, const GemmTune& tune) {
+  GemmShape s;
+  const int mtiles = (M + 15) / 16;
+  s.mt = mtiles >= 2 ? 2 : 1;
+  if (tune.mt == 1 || tune.mt == 2 || tune.mt == 4) s.mt = tune.mt;
+  const int mgroups = (mtiles + s.mt - 1) / s.mt;
+  // widest channel chunk that still gives every compute unit a workgroup
+  s.nt = 4;
+  while (s.nt > 1 && (ntiles / s.nt) * mgroups < 256) s.nt >>= 1;
+  if (tune.nt == 1 || tune.nt == 2 || tune.nt == 4) s.nt = tune.nt;
+  s.wpb = tune.wpb == 8 ? 8 : 16;
+  return s;
+}
+
+int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
   GemmDev d;
   d.xf = static_cast<const uint4*>(a.xf);
   d.wS = static_cast<const uint4*>(a.wS);
   d.wq = static_cast<const uint32_t*>(a.wq);
   d.sz = static_cast<const uint32_t*>(a.sz);
-  d.partial = reinterpret_cast<float4*>(a.partial);
-  d.counters = a.counters;
   d.out = static_cast<_Float16*>(a.out);
   d.ldo = a.ldo;
   d.M = a.M; d.N = a.N; d.ks_s = a.ks_s; d.G = a.G; d.KS = a.KS; d.KS_out = a.KS_out;
-  d.splits = a.splits; d.out_frag = a.out_frag;
-  d.chunks = a.ntiles / 4;
-  d.units = a.ks_s + a.G;
-  const int mblocks = (a.M + kMBlock - 1) / kMBlock;
-  const int mt = a.M <= 16 ? 1 : (a.M <= 32 ? 2 : 4);
+  d.out_frag = a.out_frag;
+  const GemmShape sh = pick_gemm_shape(a.M, a.ntiles, tune);
+  d.chunks = a.ntiles / sh.nt;
+  d.mgroups = ((a.M + 15) / 16 + sh.mt - 1) / sh.mt;
   const int bits = a.G == 0 ? 4 : a.bits;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const bool w8 = wpb_override == 8;
-#define ROSAQ_GEMM_CASE(B, T)                                              \
-  if (bits == B && mt == T)                                               \
-    return w8 ? launch_gemm_t<B, T, 8>(d, mblocks, st) : launch_gemm_t<B, T, 4>(d, mblocks, st);
-  ROSAQ_GEMM_CASE(4, 1) ROSAQ_GEMM_CASE(4, 2) ROSAQ_GEMM_CASE(4, 4)
-  ROSAQ_GEMM_CASE(3, 1) ROSAQ_GEMM_CASE(3, 2) ROSAQ_GEMM_CASE(3, 4)
-#undef ROSAQ_GEMM_CASE
-  set_error("no kernel for this bits / M combination");
+#define ROSAQ_CASE(B, MT_, NT_, W)                                              \
+  if (bits == B && sh.mt == MT_ && sh.nt == NT_ && sh.wpb == W)                \
+    return launch_gemm_t<B, MT_, NT_, W>(d, st);
+#define ROSAQ_CASES(B)                                                          \
+  ROSAQ_CASE(B, 1, 1, 8) ROSAQ_CASE(B, 1, 2, 8) ROSAQ_CASE(B, 1, 4, 8)          \
+  ROSAQ_CASE(B, 2, 1, 8) ROSAQ_CASE(B, 2, 2, 8) ROSAQ_CASE(B, 2, 4, 8)          \
+  ROSAQ_CASE(B, 4, 1, 8) ROSAQ_CASE(B, 4, 2, 8) ROSAQ_CASE(B, 4, 4, 8)          \
+  ROSAQ_CASE(B, 1, 1, 16) ROSAQ_CASE(B, 1, 2, 16) ROSAQ_CASE(B, 1, 4, 16)       \
+  ROSAQ_CASE(B, 2, 1, 16) ROSAQ_CASE(B, 2, 2, 16) ROSAQ_CASE(B, 2, 4, 16)       \
+  ROSAQ_CASE(B, 4, 1, 16) ROSAQ_CASE(B, 4, 2, 16)
+  ROSAQ_CASES(4)
+  ROSAQ_CASES(3)
+#undef ROSAQ_CASES
+#undef ROSAQ_CASE
+  set_error("no kernel for this bits / tile combination");
   return ROSAQ_ERR_ARG;
 }
 

@@ -87,7 +87,7 @@ def test_call_argument_errors_on_host_only_handle():
     X, Y, WS = 0x1000, 0x2000, 0x4000      # never dereferenced: every call fails validation first
     assert _code(lambda: B.rosaq_linear(p, 0, 4, 256, Y, 16, WS, ws)) == -1
     assert _code(lambda: B.rosaq_linear(p, X, 0, 256, Y, 16, WS, ws)) == -2
-    assert _code(lambda: B.rosaq_linear(p, X, 5000, 256, Y, 16, WS, 1 << 40)) == -2
+    assert _code(lambda: B.rosaq_linear(p, X, (1 << 20) + 1, 256, Y, 16, WS, 1 << 40)) == -2
     assert _code(lambda: B.rosaq_linear(p, X, 4, 128, Y, 16, WS, ws)) == -2
     assert _code(lambda: B.rosaq_linear(p, X, 4, 256, Y, 8, WS, ws)) == -2
     assert _code(lambda: B.rosaq_linear(p, X + 2, 4, 256, Y, 16, WS, ws)) == -5
@@ -109,7 +109,8 @@ def test_call_argument_errors_on_host_only_handle():
 
 
 def test_tune_keys():
-    B.rosaq_tune("splitk", 0)
-    B.rosaq_tune("wpb", 0)
+    for k in ("mt", "nt", "wpb"):
+        B.rosaq_tune(k, 0)
+    assert _code(lambda: B.rosaq_tune("mt", 3)) == -3
     assert _code(lambda: B.rosaq_tune("wpb", 3)) == -3
     assert _code(lambda: B.rosaq_tune("nope", 1)) == -3

@@ -92,12 +92,13 @@ def test_config0_single_linear():
     p.free()
 
 
-@pytest.mark.parametrize("splitk", [1, 2, 3, 8])
-def test_split_k_variants_agree_with_oracle_and_are_deterministic(splitk):
-    print(f"case splitk={splitk}", flush=True)
+@pytest.mark.parametrize("mt,nt,wpb", [(1, 1, 8), (2, 2, 16), (4, 1, 16), (1, 4, 8), (4, 4, 8), (2, 4, 16)])
+def test_tile_variants_agree_with_oracle_and_are_deterministic(mt, nt, wpb):
+    print(f"case mt={mt} nt={nt} wpb={wpb}", flush=True)
     lay, Q, lam = make_case(7, 64, 1024, 256, 512, O.MODE_HEADWISE)
     ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_HEADWISE)
-    B.rosaq_tune("splitk", splitk)
+    for k, v in (("mt", mt), ("nt", nt), ("wpb", wpb)):
+        B.rosaq_tune(k, v)
     try:
         p = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_HEADWISE)
         y0 = run_gpu(p, lay["x"])
@@ -106,7 +107,8 @@ def test_split_k_variants_agree_with_oracle_and_are_deterministic(splitk):
             assert np.array_equal(run_gpu(p, lay["x"]).view(np.uint16), y0.view(np.uint16))
         p.free()
     finally:
-        B.rosaq_tune("splitk", 0)
+        for k in ("mt", "nt", "wpb"):
+            B.rosaq_tune(k, 0)
 
 
 def test_strided_x_and_y():
