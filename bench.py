@@ -87,6 +87,7 @@ def main():
     ap.add_argument("--mt", type=int, default=0, help="tuning aid: 16-row tiles per workgroup")
     ap.add_argument("--nt", type=int, default=0, help="tuning aid: 16-channel tiles per workgroup")
     ap.add_argument("--wpb", type=int, default=0, help="tuning aid: waves per workgroup (8 or 16)")
+    ap.add_argument("--depth", type=int, default=0, help="tuning aid: units in flight per wave (2-4)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
@@ -99,7 +100,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     B.lib()
-    for key in ("mt", "nt", "wpb"):
+    for key in ("mt", "nt", "wpb", "depth"):
         B.rosaq_tune(key, getattr(args, key))
 
     # ---- synthetic layers, packed through the C ABI --------------------------------
@@ -207,7 +208,7 @@ def main():
                    "bits": BITS, "group": GROUP, "heads": HEADS, "calls_per_step": CALLS_PER_STEP,
                    "distinct_packed_weights": len(handles), "packed_MB": round(packed_bytes / 1e6, 1),
                    "launch": "eager" if args.no_graph else "hipGraph per step",
-                   "tiles": {k: getattr(args, k) or "heuristic" for k in ("mt", "nt", "wpb")}},
+                   "tiles": {k: getattr(args, k) or "heuristic" for k in ("mt", "nt", "wpb", "depth")}},
         "us_per_call": round(us_call, 3),
         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         "tflops": round(2.0 * M * N * (D + 128) / (us_call * 1e-6) / 1e12, 2),

@@ -17,7 +17,7 @@ Q_NONE, Q_FULL, Q_HEADWISE = 0, 1, 2
 ERR_NAMES = {0: "OK", -1: "NULL", -2: "SHAPE", -3: "ARG", -4: "MODE", -5: "ALIGN",
              -6: "WORKSPACE", -7: "NONFINITE", -8: "HIP", -9: "NOMEM", -10: "HOSTONLY"}
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librosaq.so")
+LIB_PATH = os.environ.get("ROSAQ_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "librosaq.so")
 
 EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_linear", "rosaq_linear_headwise",
             "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_free",

@@ -251,6 +251,10 @@ int rosaq_tune(const char* key, int32_t value) {
     if (value != 0 && value != 8 && value != 16) return fail(ROSAQ_ERR_ARG, "wpb must be 0, 8 or 16");
     g_tune.wpb = value; return ROSAQ_OK;
   }
+  if (!std::strcmp(key, "depth")) {
+    if (value != 0 && (value < 2 || value > 4)) return fail(ROSAQ_ERR_ARG, "depth must be 0, 2, 3 or 4");
+    g_tune.depth = value; return ROSAQ_OK;
+  }
   if (!std::strcmp(key, "mt") || !std::strcmp(key, "nt")) {
     if (value != 0 && value != 1 && value != 2 && value != 4)
       return fail(ROSAQ_ERR_ARG, "tile counts must be 0, 1, 2 or 4");

@@ -61,8 +61,8 @@ struct GemmArgs {
   int bits;              // 3 or 4 (ignored when G == 0)
   int out_frag;          // 0: y row-major, 1: xhat fragment order
 };
-struct GemmTune { int mt = 0, nt = 0, wpb = 0; };   // 0 = heuristic
-struct GemmShape { int mt, nt, wpb; };
+struct GemmTune { int mt = 0, nt = 0, wpb = 0, depth = 0; };   // 0 = heuristic
+struct GemmShape { int mt, nt, wpb, depth; };
 GemmShape pick_gemm_shape(int M, int ntiles, const GemmTune& tune);
 int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream);
 int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_dev,

@@ -28,6 +28,15 @@ __device__ __forceinline__ floatx4 mfma16(half8 a, half8 b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
+// (v & mask) | magic in one VALU op.  The compiler splits this into v_and + v_or with
+// two literals; VOP3 on gfx9 takes no literal, so the mask goes in an SGPR and the
+// magic constant in a VGPR.
+__device__ __forceinline__ uint32_t and_or(uint32_t v, uint32_t mask, uint32_t magic) {
+  uint32_t r;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "s"(mask), "v"(magic));
+  return r;
+}
+
 // Eight 4-bit codes of one dword -> eight fp16 values (q - z), exactly.
 // 0x6400 | q is the fp16 number 1024 + q; 0x6400 | (q << 4) is 1024 + 16 q.
 // c_lo = -(1024 + z), c_hi = -(64 + z): both subtractions are exact in fp16.
@@ -35,10 +44,10 @@ __device__ __forceinline__ half8 dequant4(uint32_t v, half2v c_lo, half2v c_hi) 
   const uint32_t kMagic = 0x64006400u;
   const half2v sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
   const uint32_t v8 = v >> 8;
-  const half2v h0 = as_h2((v & 0x000f000fu) | kMagic) + c_lo;
-  const half2v h1 = __builtin_elementwise_fma(as_h2((v & 0x00f000f0u) | kMagic), sixteenth, c_hi);
-  const half2v h2 = as_h2((v8 & 0x000f000fu) | kMagic) + c_lo;
-  const half2v h3 = __builtin_elementwise_fma(as_h2((v8 & 0x00f000f0u) | kMagic), sixteenth, c_hi);
+  const half2v h0 = as_h2(and_or(v, 0x000f000fu, kMagic)) + c_lo;
+  const half2v h1 = __builtin_elementwise_fma(as_h2(and_or(v, 0x00f000f0u, kMagic)), sixteenth, c_hi);
+  const half2v h2 = as_h2(and_or(v8, 0x000f000fu, kMagic)) + c_lo;
+  const half2v h3 = __builtin_elementwise_fma(as_h2(and_or(v8, 0x00f000f0u, kMagic)), sixteenth, c_hi);
   return half8{h0.x, h0.y, h1.x, h1.y, h2.x, h2.y, h3.x, h3.y};
 }
 
@@ -99,7 +108,7 @@ __device__ __forceinline__ void store_fragment(const GemmDev& p, float4 v, int m
 // summed through LDS in wave order, so the result does not depend on scheduling.
 // Workgroups that share a channel chunk (different row tiles) are placed on one XCD
 // so that the weights are fetched from HBM once and found in that XCD's L2 after.
-template <int BITS, int MT, int NT, int WPB>
+template <int BITS, int MT, int NT, int WPB, int DEPTH>
 __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
   __shared__ float4 red[WPB][NT * MT][64];
 
@@ -109,6 +118,9 @@ __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
   const int chunk = xcd + 8 * (local / p.mgroups);
   const int mg = local % p.mgroups;
   if (chunk >= p.chunks) return;
+#ifdef ROSAQ_PROBE_EMPTY
+  if (p.M > 0) return;
+#endif
   const int tile0 = chunk * NT;
   const int mtile0 = mg * MT;
 
@@ -126,31 +138,48 @@ __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
     xa[mt] = p.xf + (static_cast<size_t>(mtile >> 2) * p.KS * 4 + (mtile & 3)) * 64 + lane;
   }
 
-  // ---- fp16 units --------------------------------------------------------------
-  for (int u = wave; u < p.ks_s; u += WPB) {
-    half8 a[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) a[mt] = as_h8(xa[mt][static_cast<size_t>(u) * 256]);
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const half8 b = as_h8(p.wS[(static_cast<size_t>(tile0 + nt) * p.ks_s + u) * 64 + lane]);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = mfma16(a[mt], b, acc[nt][mt]);
-    }
-  }
-
-  // ---- low-bit units, two in flight per wave -----------------------------------------
+  // Per-wave work list: fp16 k-steps u = wave, wave + WPB, ... and low-bit groups
+  // g = g_first, g_first + WPB, ... (unit ks_s + g belongs to wave (ks_s + g) % WPB).
+  // Loads run two units ahead of the MFMAs; everything a wave needs first is
+  // requested before it waits for anything, in the order it will be consumed.
+  struct StepRegs {
+    uint4 a[MT];
+    uint4 b[NT];
+  };
   struct GroupRegs {
     uint32_t cw[NT][4];
     uint32_t sz[NT];
     uint4 a[4][MT];
+  };
+  auto load_step = [&](int u, StepRegs& r) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+      r.b[nt] = p.wS[(static_cast<size_t>(tile0 + nt) * p.ks_s + u) * 64 + lane];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) r.a[mt] = xa[mt][static_cast<size_t>(u) * 256];
+  };
+#ifdef ROSAQ_PROBE_NO_X
+#define ROSAQ_XLOAD(dst, src) dst = make_uint4(lane, 1, 2, 3)
+#else
+#define ROSAQ_XLOAD(dst, src) dst = src
+#endif
+  auto compute_step = [&](const StepRegs& r) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        acc[nt][mt] = mfma16(as_h8(r.a[mt]), as_h8(r.b[nt]), acc[nt][mt]);
   };
   auto load_group = [&](int g, GroupRegs& r) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       const size_t fi = (static_cast<size_t>(tile0 + nt) * p.G + g) * 64 + lane;
       if (BITS == 4) {
+#ifdef ROSAQ_PROBE_NO_W
+        const uint4 c = make_uint4(fi, 5, 6, 7);
+#else
         const uint4 c = reinterpret_cast<const uint4*>(p.wq)[fi];
+#endif
         r.cw[nt][0] = c.x; r.cw[nt][1] = c.y; r.cw[nt][2] = c.z; r.cw[nt][3] = c.w;
       } else {
         r.cw[nt][0] = p.wq[fi * 3 + 0];
@@ -164,9 +193,19 @@ __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) r.a[t][mt] = xa[mt][(ks0 + t) * 256];
+      for (int mt = 0; mt < MT; ++mt) ROSAQ_XLOAD(r.a[t][mt], xa[mt][(ks0 + t) * 256]);
   };
   auto compute_group = [&](const GroupRegs& r) {
+#ifdef ROSAQ_PROBE_NO_COMPUTE
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          acc[nt][mt][t] += __builtin_bit_cast(float, r.cw[nt][t] ^ r.a[t][mt].x ^ r.a[t][mt].y ^ r.a[t][mt].z ^ r.a[t][mt].w ^ r.sz[nt]);
+    return;
+#endif
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       const half2v sz2 = as_h2(r.sz[nt]);
@@ -191,17 +230,46 @@ __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
       for (int mt = 0; mt < MT; ++mt) acc[nt][mt] += s * tmp[mt];
     }
   };
-  // unit u = ks_s + g belongs to wave u % WPB
-  const int g_first = (wave + WPB - p.ks_s % WPB) % WPB;
-  for (int g = g_first; g < p.G; g += 2 * WPB) {
-    GroupRegs r0, r1;
-    load_group(g, r0);
-    const bool two = g + WPB < p.G;
-    if (two) load_group(g + WPB, r1);
-    compute_group(r0);
-    if (two) compute_group(r1);
+
+  const int ks_s = p.ks_s, G = p.G;
+  int u = wave;
+  int g = (wave + WPB - ks_s % WPB) % WPB;
+  StepRegs s0, s1;
+  GroupRegs r[DEPTH];
+  if (u < ks_s) load_step(u, s0);
+  if (u + WPB < ks_s) load_step(u + WPB, s1);
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d)
+    if (g + d * WPB < G) load_group(g + d * WPB, r[d]);
+  for (; u < ks_s; u += 2 * WPB) {
+    compute_step(s0);
+    if (u + 2 * WPB < ks_s) load_step(u + 2 * WPB, s0);
+    if (u + WPB < ks_s) {
+      compute_step(s1);
+      if (u + 3 * WPB < ks_s) load_step(u + 3 * WPB, s1);
+    }
+  }
+  for (; g < G; g += DEPTH * WPB) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      if (g + d * WPB < G) {
+        compute_group(r[d]);
+        if (g + (d + DEPTH) * WPB < G) load_group(g + (d + DEPTH) * WPB, r[d]);
+      }
+    }
   }
 
+#ifdef ROSAQ_PROBE_NO_EPI
+  {
+    float t = 0.f;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) t += acc[nt][mt][0] + acc[nt][mt][1] + acc[nt][mt][2] + acc[nt][mt][3];
+    if (t == 12345.678f) p.out[lane] = static_cast<_Float16>(t);
+    return;
+  }
+#endif
   // ---- sum the waves of this workgroup through LDS in wave order -----------------------
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt)
@@ -251,38 +319,36 @@ __global__ __launch_bounds__(256) void gather_kernel(const _Float16* __restrict_
   xf[idx] = v;
 }
 
-// Head-wise rotation (Eq. 6): per head h and 64-row block, xhat_h = x_h fp16(Q_h)
-// as 4 x 8 MFMA tiles, scattered to the storage position of each rotated channel.
+// Head-wise rotation (Eq. 6): xhat_h = x_h fp16(Q_h).  One workgroup per (head,
+// 16-channel column tile, 64-row block): wave w owns row tile w, issues every load
+// it needs at once (x, Q_h fragments, storage positions), runs 4 MFMAs and scatters
+// the tile to the storage position of each rotated channel.
 __global__ __launch_bounds__(256) void rotate_headwise_kernel(
     const _Float16* __restrict__ x, int64_t ldx, int M, int KS, const uint4* __restrict__ qh,
     const int32_t* __restrict__ pos, _Float16* __restrict__ xf) {
   const int lane = threadIdx.x & 63;
   const int mt = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int h = blockIdx.x, mb = blockIdx.y;
+  const int h = blockIdx.x >> 3, ct = blockIdx.x & 7, mb = blockIdx.y;
   const int m = mb * kMBlock + mt * 16 + (lane & 15);
-  half8 a[4];
+  uint4 a[4], b[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    uint4 v = make_uint4(0, 0, 0, 0);
+    a[t] = make_uint4(0, 0, 0, 0);
     if (m < M)
-      v = *reinterpret_cast<const uint4*>(x + static_cast<int64_t>(m) * ldx + h * kHeadDim +
-                                          t * kKStep + (lane >> 4) * 8);
-    a[t] = as_h8(v);
+      a[t] = *reinterpret_cast<const uint4*>(x + static_cast<int64_t>(m) * ldx + h * kHeadDim +
+                                             t * kKStep + (lane >> 4) * 8);
+    b[t] = qh[((static_cast<size_t>(h) * 8 + ct) * 4 + t) * 64 + lane];
   }
+  const int p = pos[h * kHeadDim + ct * 16 + (lane & 15)];
+  floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int ct = 0; ct < 8; ++ct) {
-    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < 4; ++t) acc = mfma16(as_h8(a[t]), as_h8(b[t]), acc);
+  const int ks = p >> 5, j = (p >> 3) & 3, e = p & 7;
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
-      acc = mfma16(a[t], as_h8(qh[((static_cast<size_t>(h) * 8 + ct) * 4 + t) * 64 + lane]), acc);
-    const int p = pos[h * kHeadDim + ct * 16 + (lane & 15)];
-    const int ks = p >> 5, j = (p >> 3) & 3, e = p & 7;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int lane2 = 4 * (lane >> 4) + i + 16 * j;
-      xf[(((static_cast<size_t>(mb) * KS + ks) * 4 + mt) * 64 + lane2) * 8 + e] =
-          static_cast<_Float16>(acc[i]);
-    }
+  for (int i = 0; i < 4; ++i) {
+    const int lane2 = 4 * (lane >> 4) + i + 16 * j;
+    xf[(((static_cast<size_t>(mb) * KS + ks) * 4 + mt) * 64 + lane2) * 8 + e] =
+        static_cast<_Float16>(acc[i]);
   }
 }
 
@@ -292,10 +358,10 @@ static int hip_fail(hipError_t e, const char* what) {
   return ROSAQ_ERR_HIP;
 }
 
-template <int BITS, int MT, int NT, int WPB>
+template <int BITS, int MT, int NT, int WPB, int DEPTH>
 static int launch_gemm_t(const GemmDev& d, hipStream_t st) {
   const int xblocks = ((d.chunks + 7) / 8) * 8 * d.mgroups;
-  hipLaunchKernelGGL((gemm_kernel<BITS, MT, NT, WPB>), dim3(xblocks), dim3(WPB * 64), 0, st, d);
+  hipLaunchKernelGGL((gemm_kernel<BITS, MT, NT, WPB, DEPTH>), dim3(xblocks), dim3(WPB * 64), 0, st, d);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "gemm_kernel launch");
 }
@@ -310,7 +376,21 @@ GemmShape pick_gemm_shape(int M, int ntiles, const GemmTune& tune) {
   s.nt = 4;
   while (s.nt > 1 && (ntiles / s.nt) * mgroups < 256) s.nt >>= 1;
   if (tune.nt == 1 || tune.nt == 2 || tune.nt == 4) s.nt = tune.nt;
-  s.wpb = tune.wpb == 8 ? 8 : 16;
+  s.wpb = s.mt * s.nt <= 2 ? 16 : 8;   // 16 waves leave 128 registers per lane
+  if (tune.wpb == 8) s.wpb = 8;
+  if (tune.wpb == 16 && s.mt * s.nt <= 2) s.wpb = 16;
+  if (s.mt * s.nt == 16) s.nt = 2;   // 64 x 64 tiles do not fit the register file
+  s.depth = tune.depth >= 2 && tune.depth <= 4 ? tune.depth : 2;
+  // deepest prefetch that still fits the register file without spilling
+  int max_depth = 4;
+  if (s.wpb == 8) {
+    if (s.mt == 4) max_depth = 2;
+    else if (s.mt * s.nt == 8) max_depth = 3;
+  } else {
+    if (s.mt == 2) max_depth = 2;
+    else if (s.nt == 2) max_depth = 3;
+  }
+  s.depth = std::min(s.depth, max_depth);
   return s;
 }
 
@@ -330,15 +410,16 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
   const int bits = a.G == 0 ? 4 : a.bits;
   hipStream_t st = static_cast<hipStream_t>(stream);
 #define ROSAQ_CASE(B, MT_, NT_, W)                                              \
-  if (bits == B && sh.mt == MT_ && sh.nt == NT_ && sh.wpb == W)                \
-    return launch_gemm_t<B, MT_, NT_, W>(d, st);
+  if (bits == B && sh.mt == MT_ && sh.nt == NT_ && sh.wpb == W) {              \
+    if (sh.depth == 2) return launch_gemm_t<B, MT_, NT_, W, 2>(d, st);           \
+    if (sh.depth == 3) return launch_gemm_t<B, MT_, NT_, W, 3>(d, st);           \
+    return launch_gemm_t<B, MT_, NT_, W, 4>(d, st);                              \
+  }
 #define ROSAQ_CASES(B)                                                          \
   ROSAQ_CASE(B, 1, 1, 8) ROSAQ_CASE(B, 1, 2, 8) ROSAQ_CASE(B, 1, 4, 8)          \
   ROSAQ_CASE(B, 2, 1, 8) ROSAQ_CASE(B, 2, 2, 8) ROSAQ_CASE(B, 2, 4, 8)          \
-  ROSAQ_CASE(B, 4, 1, 8) ROSAQ_CASE(B, 4, 2, 8) ROSAQ_CASE(B, 4, 4, 8)          \
-  ROSAQ_CASE(B, 1, 1, 16) ROSAQ_CASE(B, 1, 2, 16) ROSAQ_CASE(B, 1, 4, 16)       \
-  ROSAQ_CASE(B, 2, 1, 16) ROSAQ_CASE(B, 2, 2, 16) ROSAQ_CASE(B, 2, 4, 16)       \
-  ROSAQ_CASE(B, 4, 1, 16) ROSAQ_CASE(B, 4, 2, 16)
+  ROSAQ_CASE(B, 4, 1, 8) ROSAQ_CASE(B, 4, 2, 8)                                 \
+  ROSAQ_CASE(B, 1, 1, 16) ROSAQ_CASE(B, 1, 2, 16) ROSAQ_CASE(B, 2, 1, 16)
   ROSAQ_CASES(4)
   ROSAQ_CASES(3)
 #undef ROSAQ_CASES
@@ -361,7 +442,7 @@ int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_
 int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void* qh,
                            const int32_t* pos_dev, void* xf, void* stream) {
   const int H = D / kHeadDim, mblocks = (M + kMBlock - 1) / kMBlock;
-  hipLaunchKernelGGL(rotate_headwise_kernel, dim3(H, mblocks), dim3(256), 0,
+  hipLaunchKernelGGL(rotate_headwise_kernel, dim3(H * 8, mblocks), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<const _Float16*>(x), ldx, M,
                      D / kKStep, static_cast<const uint4*>(qh), pos_dev,
                      static_cast<_Float16*>(xf));
