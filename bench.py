@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of one hipGraph per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16", action="store_true", help="skip the fp16 GEMM comparison")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="instead of the bench, run 20 plain device copies of this size "
+                         "(reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--mt", type=int, default=0, help="tuning aid: 16-row tiles per workgroup")
     ap.add_argument("--nt", type=int, default=0, help="tuning aid: 16-channel tiles per workgroup")
     ap.add_argument("--wpb", type=int, default=0, help="tuning aid: waves per workgroup (8 or 16)")
@@ -99,6 +102,15 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.ones(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "bytes_written": n, "copies": 20}))
+        return
     B.lib()
     for key in ("mt", "nt", "wpb", "depth"):
         B.rosaq_tune(key, getattr(args, key))
