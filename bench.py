@@ -5,9 +5,12 @@ Workload (`config.workload` = "llama7b_attn_qkvo_M64_int4_headwise"): the four
 attention projections q/k/v/o of a LLaMA-7B-shaped layer, D = N = 4096, 32 heads
 x 128, x [64 x 4096] fp16, K = 128 FP16 salient channels, INT4 g128 for the rest,
 head-wise block-diagonal rotation.  One step = one decode step of the attention
-linears of a 32-layer model: 32 x 4 = 128 calls of rosaq_linear_headwise.  The
-calls cycle over `--layers` x 4 distinct packed weights whose total size exceeds
-the 256 MB last-level cache, so every call streams its weights from HBM.
+linears of a 32-layer model = 128 linears.  Per layer the q, k, v projections share
+their input and PCA rotation and go through one rosaq_linear_batch call; the output
+projection has its own input and goes through rosaq_linear_headwise (`--unbatched`
+issues four separate rosaq_linear_headwise calls instead).  The calls cycle over
+`--layers` x 4 distinct packed weights whose total size exceeds the 256 MB
+last-level cache, so every linear streams its weights from HBM.
 
 Prints ONE JSON line; `value` is algorithmic GB/s over the timed steps with all
 inputs resident in HBM.  Weights and activations are synthetic (seeded); the
@@ -44,7 +47,8 @@ def algorithmic_bytes():
     rot = 2 * 128 * 128 * HEADS
     xy = 2 * M * (D + N)
     return dict(weights=weights, rotation=rot, xy=xy, call=weights + rot + xy,
-                gemm_kernel=weights + 2 * M * D + 2 * M * N)
+                gemm_kernel=weights + 2 * M * D + 2 * M * N,
+                gemm_kernel_qkv=3 * weights + 2 * M * D + 3 * 2 * M * N)
 
 
 def cpu_baseline(seconds_target=12.0):
@@ -81,6 +85,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--layers", type=int, default=10, help="distinct layers (x4 packed weights)")
+    ap.add_argument("--unbatched", action="store_true", help="one call per linear (no q/k/v batching)")
+    ap.add_argument("--only", choices=["qkv", "o"], default=None,
+                    help="tuning aid: issue only the batched q/k/v call or only the o call of each layer")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of one hipGraph per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16", action="store_true", help="skip the fp16 GEMM comparison")
@@ -131,10 +138,23 @@ def main():
 
     stream = torch.cuda.Stream()
     calls = [(handles[i % len(handles)], ys[i % 4]) for i in range(CALLS_PER_STEP)]
+    n_layers = CALLS_PER_STEP // 4
+    qkv = [B.BatchArgs([handles[(4 * l + j) % len(handles)] for j in range(3)],
+                       [ys[j].data_ptr() for j in range(3)], [ys[j].stride(0) for j in range(3)])
+           for l in range(n_layers)]
+    wo = [handles[(4 * l + 3) % len(handles)] for l in range(n_layers)]
 
     def issue_step():
-        for h, y in calls:
-            T.linear(h, x, y, ws)
+        if args.unbatched:
+            for h, y in calls:
+                T.linear(h, x, y, ws)
+            return
+        sp = T.current_stream_ptr()
+        for l in range(n_layers):
+            if args.only != "o":
+                B.rosaq_linear_batch(qkv[l], x.data_ptr(), M, x.stride(0), ws.data_ptr(), ws.numel(), sp)
+            if args.only != "qkv":
+                T.linear(wo[l], x, ys[3], ws)
 
     def make_runner():
         if args.no_graph:
@@ -182,8 +202,15 @@ def main():
     n_calls = args.steps * CALLS_PER_STEP
     us_call = wall / n_calls * 1e6
     gbs = ab["call"] * n_calls / wall / 1e9
-    us_gemm = ev_gemm / n_calls * 1e6
-    gemm_gbs = ab["gemm_kernel"] / (us_gemm * 1e-6) / 1e9
+    # per launch of the dominant kernel: unbatched, every launch is one linear; batched, a
+    # layer issues one q/k/v launch and one o launch (the mean launch moves half of both)
+    launches = n_calls if args.unbatched else n_calls // 2
+    gemm_bytes = ab["gemm_kernel"] if args.unbatched else (ab["gemm_kernel_qkv"] + ab["gemm_kernel"]) // 2
+    if args.only:
+        launches = n_calls // 4
+        gemm_bytes = ab["gemm_kernel_qkv"] if args.only == "qkv" else ab["gemm_kernel"]
+    us_gemm = ev_gemm / launches * 1e6
+    gemm_gbs = gemm_bytes / (us_gemm * 1e-6) / 1e9
 
     # ---- fp16 dense GEMM on the same shape, same cold-weight protocol ----------------
     fp16 = None
@@ -220,17 +247,19 @@ def main():
                    "bits": BITS, "group": GROUP, "heads": HEADS, "calls_per_step": CALLS_PER_STEP,
                    "distinct_packed_weights": len(handles), "packed_MB": round(packed_bytes / 1e6, 1),
                    "launch": "eager" if args.no_graph else "hipGraph per step",
+                   "calls": "4 x rosaq_linear_headwise per layer" if args.unbatched else
+                            "rosaq_linear_batch(q,k,v) + rosaq_linear_headwise(o) per layer",
                    "tiles": {k: getattr(args, k) or "heuristic" for k in ("mt", "nt", "wpb", "depth")}},
-        "us_per_call": round(us_call, 3),
+        "us_per_linear": round(us_call, 3),
         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         "tflops": round(2.0 * M * N * (D + 128) / (us_call * 1e-6) / 1e12, 2),
         "event_ms_per_step": round(ev / args.steps * 1e3, 5),
-        "rotation_kernel_us": round(ev_rot / n_calls * 1e6, 3),
+        "rotation_kernel_us": round(ev_rot / launches * 1e6, 3),
         "pack_seconds_per_layer": round(t_pack / len(handles), 3),
         "fp16_gemm": fp16,
         "roofline": {"kernel": "gemm_kernel", "bound": "hbm", "achieved": round(gemm_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None, "bytes_per_launch": ab["gemm_kernel"],
+                     "traffic": None, "bytes_per_launch": gemm_bytes, "launches_per_step": launches // args.steps,
                      "us_per_launch": round(us_gemm, 3)},
     }
     if not args.no_cpu_baseline:

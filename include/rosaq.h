@@ -106,6 +106,20 @@ int rosaq_linear_headwise(const rosaq_packed_t* p, const void* x_dev, int32_t M,
                           void* y_dev, int64_t ldy, void* ws_dev, size_t ws_bytes,
                           void* hip_stream);
 
+/* rosaq_linear_batch - up to 4 layers that read the same input through the same
+ * rotation, in one pass: y_i = (x Q) What_i^T.  The query, key and value projections
+ * of an attention block share their input activations and hence their PCA (Eq. 5 feeds
+ * the same Z to W^Q, W^K, W^V), as do the up and gate projections of the FFN (weight
+ * splitting appendix): xhat is computed once and all layers' weights stream in one launch.
+ *   layers HOST array of `count` handles packed with identical D, K, bits, q_mode, Q
+ *          and eigenvalues (checked through a fingerprint taken at pack time)
+ *   y_dev  HOST array of `count` DEVICE pointers, y_dev[i] fp16 [M x N_i], row stride ldy[i]
+ * Other arguments and rules as rosaq_linear; the workspace size is that of layers[0].
+ * Serves every q_mode.  Errors: those of rosaq_linear, ARG (count), MODE (layers differ). */
+int rosaq_linear_batch(const rosaq_packed_t* const* layers, int32_t count, const void* x_dev,
+                       int32_t M, int64_t ldx, void* const* y_dev, const int64_t* ldy,
+                       void* ws_dev, size_t ws_bytes, void* hip_stream);
+
 /* Shape and storage facts of a handle (any output pointer may be NULL). */
 int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* K,
                       int32_t* bits, int32_t* group, int32_t* q_mode,

@@ -20,6 +20,7 @@ ERR_NAMES = {0: "OK", -1: "NULL", -2: "SHAPE", -3: "ARG", -4: "MODE", -5: "ALIGN
 LIB_PATH = os.environ.get("ROSAQ_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "librosaq.so")
 
 EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_linear", "rosaq_linear_headwise",
+            "rosaq_linear_batch",
             "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_free",
             "rosaq_last_error"]
 
@@ -63,6 +64,9 @@ def lib() -> C.CDLL:
         for f in (L.rosaq_linear, L.rosaq_linear_headwise):
             f.argtypes = [vp, vp, i32, i64, vp, i64, vp, sz, vp]
             f.restype = C.c_int
+        L.rosaq_linear_batch.argtypes = [C.POINTER(vp), i32, vp, i32, i64, C.POINTER(vp),
+                                         C.POINTER(i64), vp, sz, vp]
+        L.rosaq_linear_batch.restype = C.c_int
         L.rosaq_packed_info.argtypes = [vp] + [C.POINTER(i32)] * 6 + [C.POINTER(sz)]
         L.rosaq_packed_info.restype = C.c_int
         L.rosaq_packed_export.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -157,6 +161,24 @@ def rosaq_linear(p: Packed, x_ptr: int, M: int, ldx: int, y_ptr: int, ldy: int, 
 def rosaq_linear_headwise(p: Packed, x_ptr: int, M: int, ldx: int, y_ptr: int, ldy: int, ws_ptr: int,
                           ws_bytes: int, stream: int = 0):
     _check(lib().rosaq_linear_headwise(p.handle, x_ptr, M, ldx, y_ptr, ldy, ws_ptr, ws_bytes, stream))
+
+
+class BatchArgs:
+    """Marshalled argument arrays of one rosaq_linear_batch call (reusable)."""
+
+    def __init__(self, layers, y_ptrs, ldys):
+        n = len(layers)
+        self.count = n
+        self.layers = (C.c_void_p * n)(*[p.handle.value for p in layers])
+        self.ys = (C.c_void_p * n)(*y_ptrs)
+        self.ldys = (C.c_int64 * n)(*ldys)
+        self._keep = list(layers)
+
+
+def rosaq_linear_batch(args: BatchArgs, x_ptr: int, M: int, ldx: int, ws_ptr: int, ws_bytes: int,
+                       stream: int = 0):
+    _check(lib().rosaq_linear_batch(args.layers, args.count, x_ptr, M, ldx, args.ys, args.ldys,
+                                    ws_ptr, ws_bytes, stream))
 
 
 def rosaq_tune(key: str, value: int):

@@ -127,21 +127,73 @@ static int check_call(const rosaq_packed_t* p, const void* x, int32_t M, int64_t
   *plan = plan_workspace(*p, M);
   if (!ws || ws_bytes < plan->total) return fail(ROSAQ_ERR_WORKSPACE, "workspace missing or too small");
   if (reinterpret_cast<uintptr_t>(ws) % 256) return fail(ROSAQ_ERR_ALIGN, "workspace must be 256-byte aligned");
-  if (p->host_only) return fail(ROSAQ_ERR_HOSTONLY, "handle was packed with host_only");
   return ROSAQ_OK;
 }
 
-static int run_main_gemm(const rosaq_packed_t* p, const WsPlan& w, int M, void* y, int64_t ldy,
-                         char* ws, void* stream) {
-  const Canonical& c = p->c;
+static int check_device(const rosaq_packed_t* const* ps, int count) {
+  for (int i = 0; i < count; ++i)
+    if (ps[i]->host_only) return fail(ROSAQ_ERR_HOSTONLY, "handle was packed with host_only");
+  return ROSAQ_OK;
+}
+
+// y_i = xhat W_i^T for `count` layers that share the xhat fragments in the workspace.
+static int run_main_gemm(const rosaq_packed_t* const* ps, int count, const WsPlan& w, int M,
+                         void* const* ys, const int64_t* ldys, char* ws, void* stream) {
+  const Canonical& c = ps[0]->c;
   GemmArgs a{};
   a.xf = ws + (c.q_mode == ROSAQ_Q_FULL ? w.xf_b : w.xf_a);
-  a.wS = p->d_wS; a.wq = p->d_wq; a.sz = p->d_sz;
-  a.out = y; a.ldo = ldy; a.M = M; a.N = c.N;
-  a.ntiles = padded_tiles(c.N);
+  a.nseg = count;
+  for (int i = 0; i < count; ++i) {
+    const rosaq_packed_t* p = ps[i];
+    a.seg[i].wS = p->d_wS; a.seg[i].wq = p->d_wq; a.seg[i].sz = p->d_sz;
+    a.seg[i].out = ys[i]; a.seg[i].ldo = ldys[i]; a.seg[i].N = p->c.N;
+    a.seg[i].ntiles = padded_tiles(p->c.N);
+  }
+  a.M = M;
   a.ks_s = c.K / kKStep; a.G = c.G; a.KS = c.D / kKStep; a.KS_out = 0;
   a.bits = c.bits; a.out_frag = 0;
   return launch_gemm(a, g_tune, stream);
+}
+
+// x -> xhat fragments in the workspace (gather / head-wise blocks / dense rotation).
+static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_dev, int M,
+                        int64_t ldx, char* ws, void* hip_stream) {
+  const Canonical& c = p->c;
+  if (c.q_mode == ROSAQ_Q_HEADWISE)
+    return launch_rotate_headwise(x_dev, ldx, M, c.D, p->d_qf, p->d_pos, ws + w.xf_a, hip_stream);
+  if (c.q_mode == ROSAQ_Q_NONE)
+    return launch_gather(x_dev, ldx, M, c.D, p->d_perm, ws + w.xf_a, hip_stream);
+  // xhat = x fp16(Q): a dense fp16 contraction, run as an all-fp16 layer whose
+  // "weight" is Q^T with rows already in storage order
+  int rc = launch_gather(x_dev, ldx, M, c.D, nullptr, ws + w.xf_a, hip_stream);
+  if (rc != ROSAQ_OK) return rc;
+  GemmArgs a{};
+  a.xf = ws + w.xf_a;
+  a.nseg = 1;
+  a.seg[0].wS = p->d_qf; a.seg[0].wq = nullptr; a.seg[0].sz = nullptr;
+  a.seg[0].out = ws + w.xf_b; a.seg[0].ldo = 0; a.seg[0].N = c.D;
+  a.seg[0].ntiles = padded_tiles(c.D);
+  a.M = M;
+  a.ks_s = c.D / kKStep; a.G = 0; a.KS = c.D / kKStep; a.KS_out = c.D / kKStep;
+  a.bits = 4; a.out_frag = 1;
+  return launch_gemm(a, g_tune, hip_stream);
+}
+
+static int run_call(const rosaq_packed_t* const* ps, int count, const void* x_dev, int M,
+                    int64_t ldx, void* const* ys, const int64_t* ldys, char* ws, const WsPlan& w,
+                    void* hip_stream) {
+  if (g_tune_stages & 1) {
+    const int rc = run_prologue(ps[0], w, x_dev, M, ldx, ws, hip_stream);
+    if (rc != ROSAQ_OK) return rc;
+  }
+  if (!(g_tune_stages & 2)) return ROSAQ_OK;
+  return run_main_gemm(ps, count, w, M, ys, ldys, ws, hip_stream);
+}
+
+static uint64_t fnv1a(uint64_t h, const void* data, size_t n) {
+  const unsigned char* b = static_cast<const unsigned char*>(data);
+  for (size_t i = 0; i < n; ++i) { h ^= b[i]; h *= 1099511628211ull; }
+  return h;
 }
 
 }  // namespace rosaq
@@ -162,6 +214,15 @@ int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_pack
     rc = pack_host(*desc, &p->c, &err);
   } catch (const std::bad_alloc&) { rc = ROSAQ_ERR_NOMEM; err = "out of host memory"; }
   if (rc != ROSAQ_OK) { delete p; return fail(rc, err); }
+  {
+    uint64_t h = fnv1a(1469598103934665603ull, &desc->q_mode, sizeof(desc->q_mode));
+    h = fnv1a(h, p->c.perm.data(), p->c.perm.size() * sizeof(int32_t));
+    if (desc->q_mode == ROSAQ_Q_FULL)
+      h = fnv1a(h, desc->Q, sizeof(float) * desc->in_features * static_cast<size_t>(desc->in_features));
+    else if (desc->q_mode == ROSAQ_Q_HEADWISE)
+      h = fnv1a(h, desc->Q, sizeof(float) * desc->in_features * static_cast<size_t>(kHeadDim));
+    p->rot_fingerprint = h;
+  }
   if (!desc->host_only) {
     rc = upload(p, desc->Q, static_cast<hipStream_t>(hip_stream));
     if (rc != ROSAQ_OK) { rosaq_free(p); return rc; }
@@ -179,30 +240,9 @@ int rosaq_linear(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t 
                  int64_t ldy, void* ws_dev, size_t ws_bytes, void* hip_stream) {
   WsPlan w;
   int rc = check_call(p, x_dev, M, ldx, y_dev, ldy, ws_dev, ws_bytes, false, &w);
+  if (rc == ROSAQ_OK) rc = check_device(&p, 1);
   if (rc != ROSAQ_OK) return rc;
-  const Canonical& c = p->c;
-  char* ws = static_cast<char*>(ws_dev);
-  if (!(g_tune_stages & 1)) {
-    // timing aid: reuse the xhat fragments a previous call left in the workspace
-  } else if (c.q_mode == ROSAQ_Q_NONE) {
-    rc = launch_gather(x_dev, ldx, M, c.D, p->d_perm, ws + w.xf_a, hip_stream);
-    if (rc != ROSAQ_OK) return rc;
-  } else {
-    // xhat = x fp16(Q): a dense fp16 contraction, run as an all-fp16 layer whose
-    // "weight" is Q^T with rows already in storage order
-    rc = launch_gather(x_dev, ldx, M, c.D, nullptr, ws + w.xf_a, hip_stream);
-    if (rc != ROSAQ_OK) return rc;
-    GemmArgs a{};
-    a.xf = ws + w.xf_a; a.wS = p->d_qf; a.wq = nullptr; a.sz = nullptr;
-    a.out = ws + w.xf_b; a.ldo = 0; a.M = M; a.N = c.D;
-    a.ntiles = padded_tiles(c.D);
-    a.ks_s = c.D / kKStep; a.G = 0; a.KS = c.D / kKStep; a.KS_out = c.D / kKStep;
-    a.bits = 4; a.out_frag = 1;
-    rc = launch_gemm(a, g_tune, hip_stream);
-    if (rc != ROSAQ_OK) return rc;
-  }
-  if (!(g_tune_stages & 2)) return ROSAQ_OK;
-  return run_main_gemm(p, w, M, y_dev, ldy, ws, hip_stream);
+  return run_call(&p, 1, x_dev, M, ldx, &y_dev, &ldy, static_cast<char*>(ws_dev), w, hip_stream);
 }
 
 int rosaq_linear_headwise(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t ldx,
@@ -210,14 +250,33 @@ int rosaq_linear_headwise(const rosaq_packed_t* p, const void* x_dev, int32_t M,
                           void* hip_stream) {
   WsPlan w;
   int rc = check_call(p, x_dev, M, ldx, y_dev, ldy, ws_dev, ws_bytes, true, &w);
+  if (rc == ROSAQ_OK) rc = check_device(&p, 1);
   if (rc != ROSAQ_OK) return rc;
-  char* ws = static_cast<char*>(ws_dev);
-  if (g_tune_stages & 1) {
-    rc = launch_rotate_headwise(x_dev, ldx, M, p->c.D, p->d_qf, p->d_pos, ws + w.xf_a, hip_stream);
+  return run_call(&p, 1, x_dev, M, ldx, &y_dev, &ldy, static_cast<char*>(ws_dev), w, hip_stream);
+}
+
+int rosaq_linear_batch(const rosaq_packed_t* const* layers, int32_t count, const void* x_dev,
+                       int32_t M, int64_t ldx, void* const* y_dev, const int64_t* ldy,
+                       void* ws_dev, size_t ws_bytes, void* hip_stream) {
+  if (!layers || !y_dev || !ldy) return fail(ROSAQ_ERR_NULL, "layers, y_dev or ldy is NULL");
+  if (count < 1 || count > kMaxBatch) return fail(ROSAQ_ERR_ARG, "count must be between 1 and 4");
+  for (int i = 0; i < count; ++i)
+    if (!layers[i]) return fail(ROSAQ_ERR_NULL, "a layer handle is NULL");
+  const rosaq_packed_t* p0 = layers[0];
+  for (int i = 1; i < count; ++i) {
+    const Canonical& a = layers[i]->c;
+    if (a.D != p0->c.D || a.K != p0->c.K || a.bits != p0->c.bits || a.q_mode != p0->c.q_mode ||
+        layers[i]->rot_fingerprint != p0->rot_fingerprint)
+      return fail(ROSAQ_ERR_MODE, "layers of a batch must share D, K, bits and the rotation");
+  }
+  WsPlan w;
+  for (int i = 0; i < count; ++i) {
+    const int rc = check_call(layers[i], x_dev, M, ldx, y_dev[i], ldy[i], ws_dev, ws_bytes,
+                              p0->c.q_mode == ROSAQ_Q_HEADWISE, &w);
     if (rc != ROSAQ_OK) return rc;
   }
-  if (!(g_tune_stages & 2)) return ROSAQ_OK;
-  return run_main_gemm(p, w, M, y_dev, ldy, ws, hip_stream);
+  if (check_device(layers, count) != ROSAQ_OK) return ROSAQ_ERR_HOSTONLY;
+  return run_call(layers, count, x_dev, M, ldx, y_dev, ldy, static_cast<char*>(ws_dev), w, hip_stream);
 }
 
 int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* K, int32_t* bits,
@@ -248,11 +307,12 @@ int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t*
 int rosaq_tune(const char* key, int32_t value) {
   if (!key) return fail(ROSAQ_ERR_NULL, "key is NULL");
   if (!std::strcmp(key, "wpb")) {
-    if (value != 0 && value != 8 && value != 16) return fail(ROSAQ_ERR_ARG, "wpb must be 0, 8 or 16");
+    if (value != 0 && value != 4 && value != 8 && value != 16)
+      return fail(ROSAQ_ERR_ARG, "wpb must be 0, 4, 8 or 16");
     g_tune.wpb = value; return ROSAQ_OK;
   }
   if (!std::strcmp(key, "depth")) {
-    if (value != 0 && (value < 2 || value > 4)) return fail(ROSAQ_ERR_ARG, "depth must be 0, 2, 3 or 4");
+    if (value < 0 || value > 4) return fail(ROSAQ_ERR_ARG, "depth must be 0 to 4");
     g_tune.depth = value; return ROSAQ_OK;
   }
   if (!std::strcmp(key, "mt") || !std::strcmp(key, "nt")) {

@@ -45,15 +45,21 @@ struct DeviceImage {
 void build_device_image(const Canonical& c, const float* Q, DeviceImage* img);
 
 // ---- kernel launchers (rosaq_kernels.hip) -------------------------------------
-struct GemmArgs {
-  const void* xf;        // xhat fragments  [mblocks][KS][4][64] x 16 B
+constexpr int kMaxBatch = 4;   // layers per launch that share one rotated input
+struct GemmSegArgs {
   const void* wS;        // fp16 fragments  [ntiles][ks_s][64]   x 16 B
   const void* wq;        // low-bit fragments
   const void* sz;        // scale/zero pairs
   void* out;             // y (row-major fp16) or xhat fragments
   int64_t ldo;           // leading dimension of y
-  int M, N;              // valid rows / output channels
+  int N;                 // valid output channels
   int ntiles;            // 16-channel tiles in the weight image (multiple of 8)
+};
+struct GemmArgs {
+  const void* xf;        // xhat fragments  [mblocks][KS][4][64] x 16 B
+  GemmSegArgs seg[kMaxBatch];
+  int nseg;
+  int M;                 // valid rows
   int ks_s;              // fp16 k-steps (K/32)
   int G;                 // low-bit groups
   int KS;                // k-steps of the xf operand (D/32)
@@ -63,7 +69,7 @@ struct GemmArgs {
 };
 struct GemmTune { int mt = 0, nt = 0, wpb = 0, depth = 0; };   // 0 = heuristic
 struct GemmShape { int mt, nt, wpb, depth; };
-GemmShape pick_gemm_shape(int M, int ntiles, const GemmTune& tune);
+GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tune);
 int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream);
 int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_dev,
                   void* xf, void* stream);
@@ -87,4 +93,5 @@ struct rosaq_packed {
   void* d_qf = nullptr;
   int32_t* d_perm = nullptr;
   int32_t* d_pos = nullptr;
+  uint64_t rot_fingerprint = 0;   // hash of (q_mode, Q, storage order): equal => same xhat
 };

@@ -13,6 +13,9 @@
 // fetches a fragment with one global_load_dwordx4 per lane, 1 KiB contiguous.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <cmath>
+
 #include "rosaq_internal.h"
 
 namespace rosaq {
@@ -65,28 +68,36 @@ __device__ __forceinline__ half8 dequant3(uint32_t lo, uint32_t hi, int t, half2
   return half8{h[0].x, h[0].y, h[1].x, h[1].y, h[2].x, h[2].y, h[3].x, h[3].y};
 }
 
-struct GemmDev {
-  const uint4* xf;
+// One packed layer inside a launch.  A launch covers up to kMaxBatch layers that
+// share the rotated input (e.g. the q, k, v projections of one attention block).
+struct GemmSeg {
   const uint4* wS;
   const uint32_t* wq;
   const uint32_t* sz;
   _Float16* out;
   int64_t ldo;
-  int M, N, ks_s, G, KS, KS_out, out_frag, chunks, mgroups;
+  int N;
+  int chunk_end;     // exclusive prefix sum of channel chunks over the layers
+};
+struct GemmDev {
+  const uint4* xf;
+  GemmSeg seg[kMaxBatch];
+  int nseg;
+  int M, ks_s, G, KS, KS_out, out_frag, chunks, mgroups;
 };
 
 // Store one accumulator fragment of row tile `mtile` (16 rows) and channel tile
 // `tile`: lane holds rows 4*(lane/16)+i, column lane%16.
-__device__ __forceinline__ void store_fragment(const GemmDev& p, float4 v, int mtile, int tile,
-                                               int lane) {
+__device__ __forceinline__ void store_fragment(const GemmDev& p, const GemmSeg& sg, float4 v,
+                                               int mtile, int tile, int lane) {
   const int n = tile * kTileN + (lane & 15);
-  if (n >= p.N) return;
+  if (n >= sg.N) return;
   const float vv[4] = {v.x, v.y, v.z, v.w};
   if (!p.out_frag) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int m = mtile * 16 + 4 * (lane >> 4) + i;
-      if (m < p.M) p.out[static_cast<int64_t>(m) * p.ldo + n] = static_cast<_Float16>(vv[i]);
+      if (m < p.M) sg.out[static_cast<int64_t>(m) * sg.ldo + n] = static_cast<_Float16>(vv[i]);
     }
   } else {
     const int ks = n >> 5, j = (n >> 3) & 3, e = n & 7;
@@ -95,7 +106,7 @@ __device__ __forceinline__ void store_fragment(const GemmDev& p, float4 v, int m
       const int lane2 = 4 * (lane >> 4) + i + 16 * j;
       const size_t off =
           (((static_cast<size_t>(mtile >> 2) * p.KS_out + ks) * 4 + (mtile & 3)) * 64 + lane2) * 8 + e;
-      p.out[off] = static_cast<_Float16>(vv[i]);
+      sg.out[off] = static_cast<_Float16>(vv[i]);
     }
   }
 }
@@ -109,15 +120,24 @@ __device__ __forceinline__ void store_fragment(const GemmDev& p, float4 v, int m
 // Workgroups that share a channel chunk (different row tiles) are placed on one XCD
 // so that the weights are fetched from HBM once and found in that XCD's L2 after.
 template <int BITS, int MT, int NT, int WPB, int DEPTH>
-__global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
+__global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) void gemm_kernel(GemmDev p) {
   __shared__ float4 red[WPB][NT * MT][64];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int chunk = xcd + 8 * (local / p.mgroups);
+  int chunk = xcd + 8 * (local / p.mgroups);
   const int mg = local % p.mgroups;
   if (chunk >= p.chunks) return;
+  // which layer of the batch this chunk belongs to (uniform over the workgroup)
+  int si = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxBatch; ++i)
+    if (i < p.nseg && chunk >= p.seg[i - 1].chunk_end) si = i;
+  if (si > 0) chunk -= p.seg[si - 1].chunk_end;
+  GemmSeg sg;
+  sg.wS = p.seg[si].wS; sg.wq = p.seg[si].wq; sg.sz = p.seg[si].sz; sg.out = p.seg[si].out;
+  sg.ldo = p.seg[si].ldo; sg.N = p.seg[si].N; sg.chunk_end = 0;
 #ifdef ROSAQ_PROBE_EMPTY
   if (p.M > 0) return;
 #endif
@@ -154,7 +174,7 @@ __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
   auto load_step = [&](int u, StepRegs& r) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
-      r.b[nt] = p.wS[(static_cast<size_t>(tile0 + nt) * p.ks_s + u) * 64 + lane];
+      r.b[nt] = sg.wS[(static_cast<size_t>(tile0 + nt) * p.ks_s + u) * 64 + lane];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) r.a[mt] = xa[mt][static_cast<size_t>(u) * 256];
   };
@@ -178,16 +198,16 @@ __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
 #ifdef ROSAQ_PROBE_NO_W
         const uint4 c = make_uint4(fi, 5, 6, 7);
 #else
-        const uint4 c = reinterpret_cast<const uint4*>(p.wq)[fi];
+        const uint4 c = reinterpret_cast<const uint4*>(sg.wq)[fi];
 #endif
         r.cw[nt][0] = c.x; r.cw[nt][1] = c.y; r.cw[nt][2] = c.z; r.cw[nt][3] = c.w;
       } else {
-        r.cw[nt][0] = p.wq[fi * 3 + 0];
-        r.cw[nt][1] = p.wq[fi * 3 + 1];
-        r.cw[nt][2] = p.wq[fi * 3 + 2];
+        r.cw[nt][0] = sg.wq[fi * 3 + 0];
+        r.cw[nt][1] = sg.wq[fi * 3 + 1];
+        r.cw[nt][2] = sg.wq[fi * 3 + 2];
         r.cw[nt][3] = 0;
       }
-      r.sz[nt] = p.sz[(static_cast<size_t>(tile0 + nt) * p.G + g) * 16 + (lane & 15)];
+      r.sz[nt] = sg.sz[(static_cast<size_t>(tile0 + nt) * p.G + g) * 16 + (lane & 15)];
     }
     const size_t ks0 = static_cast<size_t>(p.ks_s + 4 * g);
 #pragma unroll
@@ -266,7 +286,7 @@ __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) t += acc[nt][mt][0] + acc[nt][mt][1] + acc[nt][mt][2] + acc[nt][mt][3];
-    if (t == 12345.678f) p.out[lane] = static_cast<_Float16>(t);
+    if (t == 12345.678f) sg.out[lane] = static_cast<_Float16>(t);
     return;
   }
 #endif
@@ -288,7 +308,7 @@ __global__ __launch_bounds__(WPB * 64) void gemm_kernel(GemmDev p) {
       const float4 o = red[w][slot][lane];
       v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
     }
-    store_fragment(p, v, mtile0 + slot % MT, tile0 + slot / MT, lane);
+    store_fragment(p, sg, v, mtile0 + slot % MT, tile0 + slot / MT, lane);
   }
 }
 
@@ -324,11 +344,13 @@ __global__ __launch_bounds__(256) void gather_kernel(const _Float16* __restrict_
 // it needs at once (x, Q_h fragments, storage positions), runs 4 MFMAs and scatters
 // the tile to the storage position of each rotated channel.
 __global__ __launch_bounds__(256) void rotate_headwise_kernel(
-    const _Float16* __restrict__ x, int64_t ldx, int M, int KS, const uint4* __restrict__ qh,
+    const _Float16* __restrict__ x, int64_t ldx, int M, int KS, int H, const uint4* __restrict__ qh,
     const int32_t* __restrict__ pos, _Float16* __restrict__ xf) {
   const int lane = threadIdx.x & 63;
   const int mt = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int h = blockIdx.x >> 3, ct = blockIdx.x & 7, mb = blockIdx.y;
+  // the eight column tiles of a head share x_h: keep them on one XCD (id % 8)
+  const int h = (blockIdx.x & 7) + 8 * (blockIdx.x >> 6), ct = (blockIdx.x >> 3) & 7, mb = blockIdx.y;
+  if (h >= H) return;
   const int m = mb * kMBlock + mt * 16 + (lane & 15);
   uint4 a[4], b[4];
 #pragma unroll
@@ -366,51 +388,84 @@ static int launch_gemm_t(const GemmDev& d, hipStream_t st) {
   return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "gemm_kernel launch");
 }
 
-GemmShape pick_gemm_shape(int M, int ntiles, const GemmTune& tune) {
+// Tile choice.  At M = 64 the three per-CU resources are of the same order: vector
+// memory inflow (about 120 GB/s per CU measured: the rotated activations of the
+// tile's rows plus the tile's weights), VALU dequantisation (once per tile, so row
+// splitting repeats it) and MFMA.  The model below prices a tile by
+// max(inflow, VALU + MFMA) and the launch by the number of rounds of 256 tiles.
+GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tune) {
   GemmShape s;
   const int mtiles = (M + 15) / 16;
-  s.mt = mtiles >= 2 ? 2 : 1;
+  const double k = static_cast<double>(D);
+  const double wbytes = bits == 16 ? 2.0 : (bits == 3 ? 0.46 : 0.58);   // per weight incl. scale / zero
+  double best = 1e30;
+  s.mt = s.nt = 1;
+  for (int mt = 1; mt <= 4; mt <<= 1) {
+    if (mt > 1 && mt / 2 >= mtiles) break;           // do not pad rows beyond the next tile size
+    for (int nt = 1; nt <= 4; nt <<= 1) {
+      const double tiles = static_cast<double>(ntiles / nt) * ((mtiles + mt - 1) / mt);
+      const double rounds = std::ceil(tiles / 256.0);
+      const double inflow = (mt * 16 * k * 2.0 + nt * 16 * k * wbytes) / 120e3;
+      const double valu = bits == 16 ? 0.0 : nt * k * (bits == 3 ? 2.9e-4 : 1.7e-4) + mt * nt * k * 1.3e-5;
+      const double mfma = mt * nt * k * 5.2e-5;
+      const double t = rounds * std::max(inflow, valu + mfma);
+      if (t < best * 0.999) { best = t; s.mt = mt; s.nt = nt; }
+    }
+  }
   if (tune.mt == 1 || tune.mt == 2 || tune.mt == 4) s.mt = tune.mt;
-  const int mgroups = (mtiles + s.mt - 1) / s.mt;
-  // widest channel chunk that still gives every compute unit a workgroup
-  s.nt = 4;
-  while (s.nt > 1 && (ntiles / s.nt) * mgroups < 256) s.nt >>= 1;
   if (tune.nt == 1 || tune.nt == 2 || tune.nt == 4) s.nt = tune.nt;
-  s.wpb = s.mt * s.nt <= 2 ? 16 : 8;   // 16 waves leave 128 registers per lane
-  if (tune.wpb == 8) s.wpb = 8;
-  if (tune.wpb == 16 && s.mt * s.nt <= 2) s.wpb = 16;
-  if (s.mt * s.nt == 16) s.nt = 2;   // 64 x 64 tiles do not fit the register file
-  s.depth = tune.depth >= 2 && tune.depth <= 4 ? tune.depth : 2;
+  s.wpb = 8;
+  if (tune.wpb == 16 && s.mt * s.nt <= 2) s.wpb = 16;   // 16 waves leave 128 registers per lane
+  if (tune.wpb == 4 && s.mt * s.nt >= 8) s.wpb = 4;     // one wave per SIMD: 512 registers
+  // loads in flight per wave: depth 1 variants of the small tiles fit 128 registers,
+  // so two workgroups share a CU and cover each other's latency
+  s.depth = (s.mt * s.nt <= 4 || s.mt * s.nt == 16) ? 1 : 2;
+  if (tune.depth >= 1 && tune.depth <= 4) s.depth = tune.depth;
   // deepest prefetch that still fits the register file without spilling
   int max_depth = 4;
-  if (s.wpb == 8) {
-    if (s.mt == 4) max_depth = 2;
+  if (s.wpb == 4) {
+    if (s.mt * s.nt == 16) max_depth = 3;
+  } else if (s.wpb == 8) {
+    if (s.mt * s.nt == 16) max_depth = 1;
+    else if (s.mt == 4) max_depth = 2;
     else if (s.mt * s.nt == 8) max_depth = 3;
   } else {
     if (s.mt == 2) max_depth = 2;
     else if (s.nt == 2) max_depth = 3;
   }
   s.depth = std::min(s.depth, max_depth);
+  if (s.depth == 1 && s.mt * s.nt > 4 && s.mt * s.nt < 16) s.depth = 2;
   return s;
 }
 
 int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
   GemmDev d;
   d.xf = static_cast<const uint4*>(a.xf);
-  d.wS = static_cast<const uint4*>(a.wS);
-  d.wq = static_cast<const uint32_t*>(a.wq);
-  d.sz = static_cast<const uint32_t*>(a.sz);
-  d.out = static_cast<_Float16*>(a.out);
-  d.ldo = a.ldo;
-  d.M = a.M; d.N = a.N; d.ks_s = a.ks_s; d.G = a.G; d.KS = a.KS; d.KS_out = a.KS_out;
+  d.M = a.M; d.ks_s = a.ks_s; d.G = a.G; d.KS = a.KS; d.KS_out = a.KS_out;
   d.out_frag = a.out_frag;
-  const GemmShape sh = pick_gemm_shape(a.M, a.ntiles, tune);
-  d.chunks = a.ntiles / sh.nt;
+  int ntiles_total = 0;
+  for (int i = 0; i < a.nseg; ++i) ntiles_total += a.seg[i].ntiles;
+  const GemmShape sh = pick_gemm_shape(a.M, ntiles_total, a.KS * kKStep, a.G == 0 ? 16 : a.bits, tune);
+  d.nseg = a.nseg;
+  int chunks = 0;
+  for (int i = 0; i < kMaxBatch; ++i) {
+    const GemmSegArgs& sa = a.seg[i < a.nseg ? i : 0];
+    if (i < a.nseg) chunks += sa.ntiles / sh.nt;
+    d.seg[i].wS = static_cast<const uint4*>(sa.wS);
+    d.seg[i].wq = static_cast<const uint32_t*>(sa.wq);
+    d.seg[i].sz = static_cast<const uint32_t*>(sa.sz);
+    d.seg[i].out = static_cast<_Float16*>(sa.out);
+    d.seg[i].ldo = sa.ldo;
+    d.seg[i].N = sa.N;
+    d.seg[i].chunk_end = chunks;
+  }
+  d.chunks = chunks;
   d.mgroups = ((a.M + 15) / 16 + sh.mt - 1) / sh.mt;
   const int bits = a.G == 0 ? 4 : a.bits;
   hipStream_t st = static_cast<hipStream_t>(stream);
 #define ROSAQ_CASE(B, MT_, NT_, W)                                              \
   if (bits == B && sh.mt == MT_ && sh.nt == NT_ && sh.wpb == W) {              \
+    if (sh.depth == 1) return launch_gemm_t<B, MT_, NT_, W, 1>(d, st);           \
     if (sh.depth == 2) return launch_gemm_t<B, MT_, NT_, W, 2>(d, st);           \
     if (sh.depth == 3) return launch_gemm_t<B, MT_, NT_, W, 3>(d, st);           \
     return launch_gemm_t<B, MT_, NT_, W, 4>(d, st);                              \
@@ -418,7 +473,8 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
 #define ROSAQ_CASES(B)                                                          \
   ROSAQ_CASE(B, 1, 1, 8) ROSAQ_CASE(B, 1, 2, 8) ROSAQ_CASE(B, 1, 4, 8)          \
   ROSAQ_CASE(B, 2, 1, 8) ROSAQ_CASE(B, 2, 2, 8) ROSAQ_CASE(B, 2, 4, 8)          \
-  ROSAQ_CASE(B, 4, 1, 8) ROSAQ_CASE(B, 4, 2, 8)                                 \
+  ROSAQ_CASE(B, 4, 1, 8) ROSAQ_CASE(B, 4, 2, 8) ROSAQ_CASE(B, 4, 4, 8)          \
+  ROSAQ_CASE(B, 4, 4, 4) ROSAQ_CASE(B, 4, 2, 4) ROSAQ_CASE(B, 2, 4, 4)          \
   ROSAQ_CASE(B, 1, 1, 16) ROSAQ_CASE(B, 1, 2, 16) ROSAQ_CASE(B, 2, 1, 16)
   ROSAQ_CASES(4)
   ROSAQ_CASES(3)
@@ -442,9 +498,9 @@ int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_
 int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void* qh,
                            const int32_t* pos_dev, void* xf, void* stream) {
   const int H = D / kHeadDim, mblocks = (M + kMBlock - 1) / kMBlock;
-  hipLaunchKernelGGL(rotate_headwise_kernel, dim3(H * 8, mblocks), dim3(256), 0,
+  hipLaunchKernelGGL(rotate_headwise_kernel, dim3(((H + 7) / 8) * 64, mblocks), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<const _Float16*>(x), ldx, M,
-                     D / kKStep, static_cast<const uint4*>(qh), pos_dev,
+                     D / kKStep, H, static_cast<const uint4*>(qh), pos_dev,
                      static_cast<_Float16*>(xf));
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "rotate_headwise_kernel launch");

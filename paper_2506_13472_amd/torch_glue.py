@@ -31,3 +31,16 @@ def linear(p: B.Packed, x: torch.Tensor, y: torch.Tensor | None = None,
     fn(p, x.data_ptr(), M, x.stride(0), y.data_ptr(), y.stride(0), ws.data_ptr(), ws.numel(),
        current_stream_ptr())
     return y
+
+
+def linear_batch(layers, x: torch.Tensor, ys=None, ws: torch.Tensor | None = None):
+    """[y_i] = rosaq_linear_batch(layers, x): layers share x and the rotation."""
+    M = x.shape[0]
+    if ys is None:
+        ys = [torch.empty((M, p.N), dtype=torch.float16, device=x.device) for p in layers]
+    if ws is None:
+        ws = alloc_workspace(layers[0], M)
+    args = B.BatchArgs(layers, [y.data_ptr() for y in ys], [y.stride(0) for y in ys])
+    B.rosaq_linear_batch(args, x.data_ptr(), M, x.stride(0), ws.data_ptr(), ws.numel(),
+                         current_stream_ptr())
+    return ys

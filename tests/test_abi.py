@@ -114,3 +114,26 @@ def test_tune_keys():
     assert _code(lambda: B.rosaq_tune("mt", 3)) == -3
     assert _code(lambda: B.rosaq_tune("wpb", 3)) == -3
     assert _code(lambda: B.rosaq_tune("nope", 1)) == -3
+
+
+def test_batch_argument_errors():
+    W, Q, lam, K, bits, mode = _good()
+    p = B.rosaq_pack_weights(W, Q, lam, K, bits, mode, host_only=True)
+    p2 = B.rosaq_pack_weights(W[:8], Q, lam, K, bits, mode, host_only=True)
+    lam3 = lam[::-1].copy()                       # other storage order -> other rotated input
+    p3 = B.rosaq_pack_weights(W, Q, lam3, K, bits, mode, host_only=True)
+    p4 = B.rosaq_pack_weights(W, Q, lam, K, 3, mode, host_only=True)
+    X, Y, WS = 0x1000, 0x2000, 0x4000
+    ws = B.rosaq_workspace_bytes(p, 4)
+    ok = B.BatchArgs([p, p2], [Y, Y], [16, 8])
+    assert _code(lambda: B.rosaq_linear_batch(ok, X, 4, 256, WS, ws)) == -10     # valid up to HOSTONLY
+    assert _code(lambda: B.rosaq_linear_batch(B.BatchArgs([p, p3], [Y, Y], [16, 16]), X, 4, 256, WS, ws)) == -4
+    assert _code(lambda: B.rosaq_linear_batch(B.BatchArgs([p, p4], [Y, Y], [16, 16]), X, 4, 256, WS, ws)) == -4
+    assert _code(lambda: B.rosaq_linear_batch(B.BatchArgs([p] * 5, [Y] * 5, [16] * 5), X, 4, 256, WS, ws)) == -3
+    assert _code(lambda: B.rosaq_linear_batch(B.BatchArgs([p, p2], [Y, 0], [16, 8]), X, 4, 256, WS, ws)) == -1
+    assert _code(lambda: B.rosaq_linear_batch(B.BatchArgs([p, p2], [Y, Y], [16, 4]), X, 4, 256, WS, ws)) == -2
+    assert B.lib().rosaq_linear_batch(None, 1, X, 4, 256, None, None, WS, ws, None) == -1
+    ok.count = 0
+    assert _code(lambda: B.rosaq_linear_batch(ok, X, 4, 256, WS, ws)) == -3
+    for h in (p, p2, p3, p4):
+        h.free()

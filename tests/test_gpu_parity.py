@@ -111,6 +111,30 @@ def test_tile_variants_agree_with_oracle_and_are_deterministic(mt, nt, wpb):
             B.rosaq_tune(k, 0)
 
 
+@pytest.mark.parametrize("mode,bits", [(O.MODE_HEADWISE, 4), (O.MODE_FULL, 3), (O.MODE_NONE, 4)])
+def test_batch_of_layers_sharing_the_rotation(mode, bits):
+    """q/k/v-style batch: three layers with different widths share x and Q; one launch."""
+    from paper_2506_13472_amd import torch_glue as T
+    print(f"case batch mode={mode} bits={bits}", flush=True)
+    M, D = 64, 512
+    lay, Q, lam = make_case(21, M, D, 200, 300, mode)
+    Ws = [lay["W"], synth.make_weight(31, 96, D), synth.make_weight(32, 330, D)]
+    refs = [O.pack(W, Q, lam, 128, bits, mode) for W in Ws]
+    ps = [B.rosaq_pack_weights(W, Q, lam, 128, bits, mode) for W in Ws]
+    for p, ref in zip(ps, refs):
+        check_pack(p, ref)
+    x = torch.from_numpy(lay["x"]).cuda()
+    ys = T.linear_batch(ps, x)
+    torch.cuda.synchronize()
+    for y, p, ref in zip(ys, ps, refs):
+        yh = y.cpu().numpy()
+        check_output(yh, lay["x"], Q, ref)
+        # the batched launch and the single-layer call run the same arithmetic
+        assert np.array_equal(run_gpu(p, lay["x"]).view(np.uint16), yh.view(np.uint16))
+    for p in ps:
+        p.free()
+
+
 def test_strided_x_and_y():
     from paper_2506_13472_amd import torch_glue as T
     print("case strided", flush=True)
