@@ -91,6 +91,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of one hipGraph per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16", action="store_true", help="skip the fp16 GEMM comparison")
+    ap.add_argument("--no-probe", action="store_true", help="skip the pure read-stream ceiling")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of the bench, run 20 plain device copies of this size "
                          "(reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -238,6 +239,36 @@ def main():
                 "GBps": round((2 * N * D + ab["xy"]) / (us16 * 1e-6) / 1e9, 1),
                 "rosaq_speedup": round(us16 / us_call, 3), "impl": "torch.matmul fp16 (vendor GEMM)"}
 
+    # ---- the memory system's own ceiling: a pure read stream of one linear's size ------
+    probe = None
+    if not args.no_probe:
+        pb = 10 << 20                                     # ~ one packed 4096 x 4096 INT4 layer
+        n_src = max(8, packed_bytes // pb + 1)
+        srcs = [torch.ones(pb, dtype=torch.uint8, device=dev) for _ in range(n_src)]
+        shared = torch.ones(512 << 10, dtype=torch.uint8, device=dev)       # = 64 x 4096 fp16
+        sink = torch.zeros(256 * 8 * 1024, dtype=torch.uint8, device=dev)
+        probe = {"bytes_per_launch": pb, "launch": "256 workgroups x 512 threads"}
+        for name, per_wg in (("weights_only_us", 0), ("with_256KiB_shared_per_workgroup_us", 256 << 10)):
+            def probe_step():
+                sp = T.current_stream_ptr()
+                for i in range(CALLS_PER_STEP):
+                    B.rosaq_stream_probe(srcs[i % n_src].data_ptr(), pb, shared.data_ptr(), shared.numel(),
+                                         per_wg, 256, 512, sink.data_ptr(), sink.numel(), sp)
+            with torch.cuda.stream(stream):
+                probe_step()
+                stream.synchronize()
+                if args.no_graph:
+                    runp = probe_step
+                else:
+                    gp = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(gp, stream=stream):
+                        probe_step()
+                    runp = gp.replay
+            _, evp = timed(runp, args.steps, args.warmup)
+            probe[name] = round(evp / n_calls * 1e6, 3)
+        probe["weights_only_GBps"] = round(pb / (probe["weights_only_us"] * 1e-6) / 1e9, 1)
+        del srcs
+
     out = {
         "metric": "fused ROSAQ linear HBM GB/s at M=64 (algorithmic bytes / time)",
         "value": round(gbs, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -257,6 +288,7 @@ def main():
         "rotation_kernel_us": round(ev_rot / launches * 1e6, 3),
         "pack_seconds_per_layer": round(t_pack / len(handles), 3),
         "fp16_gemm": fp16,
+        "stream_probe": probe,
         "roofline": {"kernel": "gemm_kernel", "bound": "hbm", "achieved": round(gemm_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
                      "traffic": None, "bytes_per_launch": gemm_bytes, "launches_per_step": launches // args.steps,

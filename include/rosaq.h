@@ -135,6 +135,19 @@ int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* 
 int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t* W_S,
                         uint8_t* codes, uint16_t* scales, uint16_t* zeros);
 
+/* rosaq_stream_probe - measurement aid, no arithmetic of the method: one launch of
+ * `workgroups` x `threads` in which every wave reads its own contiguous share of
+ * src_dev (src_bytes in total, 1 KiB per load) and every workgroup then reads
+ * shared_bytes_per_workgroup from the start region of shared_dev (a buffer all
+ * workgroups share, as they share the rotated activations in the GEMM).  Nothing is
+ * written unless the data matches a magic pattern.  Timing it next to the GEMM gives
+ * the memory system's own ceiling for a launch of that size and shape.
+ * All pointers DEVICE, 16-byte aligned; src_bytes a multiple of 1 KiB per wave;
+ * sink_dev at least 16 bytes per thread.  Errors: NULL, ARG, SHAPE, WORKSPACE, ALIGN, HIP. */
+int rosaq_stream_probe(const void* src_dev, size_t src_bytes, const void* shared_dev,
+                       size_t shared_bytes, size_t shared_bytes_per_workgroup, int32_t workgroups,
+                       int32_t threads, void* sink_dev, size_t sink_bytes, void* hip_stream);
+
 /* Tuning aid for benchmarks; affects later rosaq_linear* calls in this process.
  *   "mt", "nt"  16-row / 16-channel MFMA tiles per workgroup (0 = heuristic, 1, 2, 4)
  *   "wpb"     waves per workgroup splitting the contraction (0 = default, 8, 16)

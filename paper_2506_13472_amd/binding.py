@@ -20,7 +20,7 @@ ERR_NAMES = {0: "OK", -1: "NULL", -2: "SHAPE", -3: "ARG", -4: "MODE", -5: "ALIGN
 LIB_PATH = os.environ.get("ROSAQ_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "librosaq.so")
 
 EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_linear", "rosaq_linear_headwise",
-            "rosaq_linear_batch",
+            "rosaq_linear_batch", "rosaq_stream_probe",
             "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_free",
             "rosaq_last_error"]
 
@@ -67,6 +67,8 @@ def lib() -> C.CDLL:
         L.rosaq_linear_batch.argtypes = [C.POINTER(vp), i32, vp, i32, i64, C.POINTER(vp),
                                          C.POINTER(i64), vp, sz, vp]
         L.rosaq_linear_batch.restype = C.c_int
+        L.rosaq_stream_probe.argtypes = [vp, sz, vp, sz, sz, i32, i32, vp, sz, vp]
+        L.rosaq_stream_probe.restype = C.c_int
         L.rosaq_packed_info.argtypes = [vp] + [C.POINTER(i32)] * 6 + [C.POINTER(sz)]
         L.rosaq_packed_info.restype = C.c_int
         L.rosaq_packed_export.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -179,6 +181,14 @@ def rosaq_linear_batch(args: BatchArgs, x_ptr: int, M: int, ldx: int, ws_ptr: in
                        stream: int = 0):
     _check(lib().rosaq_linear_batch(args.layers, args.count, x_ptr, M, ldx, args.ys, args.ldys,
                                     ws_ptr, ws_bytes, stream))
+
+
+def rosaq_stream_probe(src_ptr: int, src_bytes: int, shared_ptr: int, shared_bytes: int,
+                       shared_bytes_per_workgroup: int, workgroups: int, threads: int,
+                       sink_ptr: int, sink_bytes: int, stream: int = 0):
+    _check(lib().rosaq_stream_probe(src_ptr, src_bytes, shared_ptr, shared_bytes,
+                                    shared_bytes_per_workgroup, workgroups, threads, sink_ptr,
+                                    sink_bytes, stream))
 
 
 def rosaq_tune(key: str, value: int):

@@ -304,6 +304,30 @@ int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t*
   return ROSAQ_OK;
 }
 
+int rosaq_stream_probe(const void* src_dev, size_t src_bytes, const void* shared_dev,
+                       size_t shared_bytes, size_t shared_bytes_per_workgroup, int32_t workgroups,
+                       int32_t threads, void* sink_dev, size_t sink_bytes, void* hip_stream) {
+  if (!src_dev || !sink_dev) return fail(ROSAQ_ERR_NULL, "src_dev or sink_dev is NULL");
+  if (workgroups < 1 || threads < 64 || threads > 1024 || threads % 64)
+    return fail(ROSAQ_ERR_ARG, "workgroups >= 1 and threads a multiple of 64 up to 1024");
+  const size_t waves = static_cast<size_t>(workgroups) * (threads / 64);
+  if (src_bytes == 0 || src_bytes % (waves * 1024))
+    return fail(ROSAQ_ERR_SHAPE, "src_bytes must be a positive multiple of 1 KiB per wave");
+  const size_t wpw = static_cast<size_t>(threads / 64) * 1024;
+  if (shared_bytes_per_workgroup % wpw || shared_bytes % 1024)
+    return fail(ROSAQ_ERR_SHAPE, "shared sizes must be multiples of 1 KiB (per wave)");
+  if (shared_bytes_per_workgroup && (!shared_dev || shared_bytes < shared_bytes_per_workgroup / (threads / 64)))
+    return fail(ROSAQ_ERR_SHAPE, "shared buffer missing or smaller than one wave's share");
+  if (sink_bytes < waves * 1024) return fail(ROSAQ_ERR_WORKSPACE, "sink smaller than 16 bytes per thread");
+  if (reinterpret_cast<uintptr_t>(src_dev) % 16 || reinterpret_cast<uintptr_t>(shared_dev) % 16 ||
+      reinterpret_cast<uintptr_t>(sink_dev) % 16)
+    return fail(ROSAQ_ERR_ALIGN, "probe buffers must be 16-byte aligned");
+  return launch_stream_probe(src_dev, shared_dev, workgroups, threads,
+                             static_cast<int>(src_bytes / (waves * 1024)),
+                             static_cast<int>(shared_bytes_per_workgroup / wpw),
+                             static_cast<int>(shared_bytes / 1024), sink_dev, hip_stream);
+}
+
 int rosaq_tune(const char* key, int32_t value) {
   if (!key) return fail(ROSAQ_ERR_NULL, "key is NULL");
   if (!std::strcmp(key, "wpb")) {

@@ -76,6 +76,9 @@ int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_
 int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void* qh,
                            const int32_t* pos_dev, void* xf, void* stream);
 
+int launch_stream_probe(const void* src, const void* shared, int workgroups, int threads, int w_kib,
+                        int x_kib, int shared_kib, void* sink, void* stream);
+
 void set_error(const std::string& s);
 
 }  // namespace rosaq

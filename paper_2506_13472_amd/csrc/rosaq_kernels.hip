@@ -374,6 +374,42 @@ __global__ __launch_bounds__(256) void rotate_headwise_kernel(
   }
 }
 
+// Measurement aid: a pure read stream.  Every wave reads `w_kib` KiB of its own from
+// `src` (1 KiB per load, eight loads in flight) and then `x_kib` KiB from a buffer
+// shared by all workgroups, and keeps nothing.  It shows what the memory system
+// delivers for a launch of the GEMM's size and shape, with no arithmetic at all.
+__global__ __launch_bounds__(1024) void stream_probe_kernel(const uint4* __restrict__ src,
+                                                            const uint4* __restrict__ shared,
+                                                            int w_kib, int x_kib, int shared_kib,
+                                                            uint4* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  const size_t gw = static_cast<size_t>(blockIdx.x) * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  uint4 acc = make_uint4(0, 0, 0, 0);
+  const uint4* wp = src + gw * w_kib * 64 + lane;
+  for (int i = 0; i < w_kib; i += 8) {
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      v[u] = i + u < w_kib ? wp[static_cast<size_t>(i + u) * 64] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+  }
+  const int start = shared_kib ? static_cast<int>((threadIdx.x >> 6) * x_kib % shared_kib) : 0;
+  for (int i = 0; i < x_kib; i += 8) {
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      int c = start + i + u;
+      if (c >= shared_kib) c -= shared_kib;
+      v[u] = i + u < x_kib ? shared[static_cast<size_t>(c) * 64 + lane] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+  }
+  // never true for the probe's fill patterns; keeps the loads alive
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345678u) sink[gw * 64 + lane] = acc;
+}
+
 // ---- launchers ------------------------------------------------------------------
 static int hip_fail(hipError_t e, const char* what) {
   set_error(std::string(what) + ": " + hipGetErrorString(e));
@@ -482,6 +518,16 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
 #undef ROSAQ_CASE
   set_error("no kernel for this bits / tile combination");
   return ROSAQ_ERR_ARG;
+}
+
+int launch_stream_probe(const void* src, const void* shared, int workgroups, int threads, int w_kib,
+                        int x_kib, int shared_kib, void* sink, void* stream) {
+  hipLaunchKernelGGL(stream_probe_kernel, dim3(workgroups), dim3(threads), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(src),
+                     static_cast<const uint4*>(shared), w_kib, x_kib, shared_kib,
+                     static_cast<uint4*>(sink));
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "stream_probe_kernel launch");
 }
 
 int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_dev, void* xf,

@@ -137,3 +137,25 @@ def test_batch_argument_errors():
     assert _code(lambda: B.rosaq_linear_batch(ok, X, 4, 256, WS, ws)) == -3
     for h in (p, p2, p3, p4):
         h.free()
+
+
+def test_stream_probe_argument_errors():
+    S, H, K = 0x10000, 0x20000, 0x30000
+    ok = dict(src_ptr=S, src_bytes=256 * 8 * 1024, shared_ptr=H, shared_bytes=512 * 1024,
+              shared_bytes_per_workgroup=8 * 1024, workgroups=256, threads=512, sink_ptr=K,
+              sink_bytes=256 * 8 * 1024)
+    def call(**kw):
+        a = dict(ok); a.update(kw)
+        return _code(lambda: B.rosaq_stream_probe(**a))
+    assert call(src_ptr=0) == -1
+    assert call(sink_ptr=0) == -1
+    assert call(threads=100) == -3
+    assert call(threads=2048) == -3
+    assert call(workgroups=0) == -3
+    assert call(src_bytes=1000) == -2
+    assert call(src_bytes=0) == -2
+    assert call(shared_bytes_per_workgroup=1024) == -2          # not 1 KiB per wave
+    assert call(shared_bytes=512, shared_bytes_per_workgroup=8 * 1024) == -2
+    assert call(shared_ptr=0) == -2
+    assert call(sink_bytes=1024) == -6
+    assert call(src_ptr=S + 4) == -5

@@ -163,3 +163,17 @@ def test_config1_attention_projection_full_size():
     y = run_gpu(p, lay["x"])
     check_output(y, lay["x"], Q, ref)
     p.free()
+
+
+def test_stream_probe_runs_and_writes_nothing():
+    print("case stream probe", flush=True)
+    n = 256 * 8 * 4 * 1024
+    src = torch.ones(n, dtype=torch.uint8, device="cuda")
+    shared = torch.full((512 * 1024,), 2, dtype=torch.uint8, device="cuda")
+    sink = torch.full((256 * 8 * 1024,), 9, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    for per_wg in (0, 64 * 1024, 512 * 1024):
+        B.rosaq_stream_probe(src.data_ptr(), n, shared.data_ptr(), shared.numel(), per_wg, 256, 512,
+                             sink.data_ptr(), sink.numel(), st)
+    torch.cuda.synchronize()
+    assert bool((sink == 9).all())
