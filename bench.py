@@ -79,6 +79,98 @@ def cpu_baseline(seconds_target=12.0):
                       f"{dt / n * 1e3:.1f} ms per call"}
 
 
+SWEEP_SHAPES = [
+    # name, D, N, bits, q_mode ("headwise" | "full" | "none"), M values
+    ("7B attn q/k/v/o, head-wise, INT4", 4096, 4096, 4, "headwise", (1, 16, 64, 256)),
+    ("7B gate/up, full 4096^2 rotation, INT3", 4096, 11008, 3, "full", (64,)),
+    ("7B down, no rotation (paper's setting), INT3", 11008, 4096, 3, "none", (64,)),
+    ("7B down, full 11008^2 rotation, INT3", 11008, 4096, 3, "full", (64,)),
+    ("13B up, full 5120^2 rotation, INT4", 5120, 13824, 4, "full", (1, 16, 64, 256)),
+    ("13B down, no rotation, INT4", 13824, 5120, 4, "none", (1, 16, 64, 256)),
+    ("13B down, full 13824^2 rotation, INT4", 13824, 5120, 4, "full", (64,)),
+]
+
+
+def shape_sweep(args):
+    """One JSON line per (shape, M): us per call of the library against a fp16 torch.matmul, both
+    cycling over enough distinct copies of the weights to stay out of the last-level cache."""
+    import torch
+    from paper_2506_13472_amd import binding as B, synth, torch_glue as T
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream()
+    modes = {"headwise": B.Q_HEADWISE, "full": B.Q_FULL, "none": B.Q_NONE}
+
+    def time_graph(step, reps):
+        with torch.cuda.stream(stream):
+            step()
+            stream.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                step()
+            for _ in range(3):
+                g.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            stream.synchronize()
+            e0.record(stream)
+            for _ in range(reps):
+                g.replay()
+            e1.record(stream)
+            stream.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    for name, D_, N_, bits, mode, Ms in SWEEP_SHAPES:
+        if args.sweep_filter and args.sweep_filter not in name:
+            continue
+        W = synth.make_weight(11, N_, D_)
+        lam = synth.descending_spectrum(13, D_, D_ // 128 if mode == "headwise" else 1)
+        Q = None
+        if mode == "headwise":
+            Q = synth.random_orthogonal_blocks(12, D_ // 128)
+        elif mode == "full":
+            Q = synth.random_orthogonal_dense(12, D_)
+        t0 = time.perf_counter()
+        base = B.rosaq_pack_weights(W, Q, lam, K, bits, modes[mode])
+        t_pack = time.perf_counter() - t0
+        copies = [base]
+        while sum(h.device_bytes for h in copies) < (320 << 20) or len(copies) < 2:
+            copies.append(B.rosaq_packed_clone(base))
+        w16 = torch.from_numpy(W).to(dev)
+        n16 = max(2, (320 << 20) // (2 * N_ * D_) + 1)
+        W16 = [w16.clone() for _ in range(n16)]
+        per_row = 2 * K + (D_ - K) * bits // 8 + 4 * (D_ - K) // GROUP
+        rot_bytes = {"headwise": 2 * 128 * D_, "full": 2 * D_ * D_, "none": 0}[mode]
+        calls = 32
+        for M_ in Ms:
+            x = torch.from_numpy(synth.make_activations(17, M_, D_)).to(dev)
+            y = torch.empty((M_, N_), dtype=torch.float16, device=dev)
+            ws = T.alloc_workspace(base, M_)
+
+            def step():
+                for i in range(calls):
+                    T.linear(copies[i % len(copies)], x, y, ws)
+
+            def step16():
+                for i in range(calls):
+                    torch.matmul(x, W16[i % n16].t(), out=y)
+            us = time_graph(step, 20) / calls * 1e6
+            B.rosaq_tune("stages", 2)
+            us_gemm = time_graph(step, 20) / calls * 1e6
+            B.rosaq_tune("stages", 3)
+            us16 = time_graph(step16, 20) / calls * 1e6
+            nbytes = per_row * N_ + rot_bytes + 2 * M_ * (D_ + N_)
+            print(json.dumps({"shape": name, "D": D_, "N": N_, "M": M_, "bits": bits, "rotation": mode,
+                              "us_per_call": round(us, 2), "us_main_gemm": round(us_gemm, 2),
+                              "algorithmic_MB": round(nbytes / 1e6, 2),
+                              "GBps": round(nbytes / us / 1e3, 1),
+                              "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                              "tflops": round(2.0 * M_ * N_ * D_ / us / 1e6, 1),
+                              "fp16_matmul_us": round(us16, 2), "speedup_vs_fp16": round(us16 / us, 2),
+                              "distinct_copies": len(copies), "pack_s": round(t_pack, 1)}), flush=True)
+        for h in copies:
+            h.free()
+        del W16, w16
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -92,6 +184,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16", action="store_true", help="skip the fp16 GEMM comparison")
     ap.add_argument("--no-probe", action="store_true", help="skip the pure read-stream ceiling")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the bench, time every MLP / attention shape of the task's configs "
+                         "(one JSON line each)")
+    ap.add_argument("--sweep-filter", default="", help="substring of the shape names to run")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of the bench, run 20 plain device copies of this size "
                          "(reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -122,6 +218,9 @@ def main():
     B.lib()
     for key in ("mt", "nt", "wpb", "depth"):
         B.rosaq_tune(key, getattr(args, key))
+    if args.sweep:
+        shape_sweep(args)
+        return
 
     # ---- synthetic layers, packed through the C ABI --------------------------------
     t_pack = time.perf_counter()

@@ -82,6 +82,12 @@ typedef struct {
  * library until rosaq_free.  Errors: NULL, SHAPE, ARG, NONFINITE, NOMEM, HIP. */
 int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_packed_t** out);
 
+/* rosaq_packed_clone - a second, independent copy of a packed layer: host arrays
+ * copied, device buffers duplicated with a device-to-device copy on hip_stream (the
+ * call waits for it).  The clone is freed with rosaq_free like any handle.
+ * Errors: NULL, NOMEM, HIP. */
+int rosaq_packed_clone(const rosaq_packed_t* src, void* hip_stream, rosaq_packed_t** out);
+
 /* Bytes of DEVICE workspace rosaq_linear* needs for M rows (0 on a bad handle). */
 size_t rosaq_workspace_bytes(const rosaq_packed_t* p, int32_t M);
 

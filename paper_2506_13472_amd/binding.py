@@ -20,7 +20,7 @@ ERR_NAMES = {0: "OK", -1: "NULL", -2: "SHAPE", -3: "ARG", -4: "MODE", -5: "ALIGN
 LIB_PATH = os.environ.get("ROSAQ_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "librosaq.so")
 
 EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_linear", "rosaq_linear_headwise",
-            "rosaq_linear_batch", "rosaq_stream_probe",
+            "rosaq_linear_batch", "rosaq_stream_probe", "rosaq_packed_clone",
             "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_free",
             "rosaq_last_error"]
 
@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
         vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
         L.rosaq_pack_weights.argtypes = [C.POINTER(PackDesc), vp, C.POINTER(vp)]
         L.rosaq_pack_weights.restype = C.c_int
+        L.rosaq_packed_clone.argtypes = [vp, vp, C.POINTER(vp)]
+        L.rosaq_packed_clone.restype = C.c_int
         L.rosaq_workspace_bytes.argtypes = [vp, i32]
         L.rosaq_workspace_bytes.restype = sz
         for f in (L.rosaq_linear, L.rosaq_linear_headwise):
@@ -137,6 +139,12 @@ def rosaq_pack_weights(W: np.ndarray, Q, eigenvalues: np.ndarray, K: int, bits: 
     d.K, d.bits, d.group, d.select_rule, d.host_only = K, bits, group, select_rule, int(host_only)
     out = C.c_void_p()
     _check(lib().rosaq_pack_weights(C.byref(d), C.c_void_p(stream), C.byref(out)))
+    return Packed(out.value)
+
+
+def rosaq_packed_clone(p: Packed, stream: int = 0) -> Packed:
+    out = C.c_void_p()
+    _check(lib().rosaq_packed_clone(p.handle, C.c_void_p(stream), C.byref(out)))
     return Packed(out.value)
 
 

@@ -5,6 +5,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <type_traits>
 
 #include "rosaq_internal.h"
 
@@ -226,6 +227,36 @@ int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_pack
   if (!desc->host_only) {
     rc = upload(p, desc->Q, static_cast<hipStream_t>(hip_stream));
     if (rc != ROSAQ_OK) { rosaq_free(p); return rc; }
+  }
+  *out = p;
+  return ROSAQ_OK;
+}
+
+int rosaq_packed_clone(const rosaq_packed_t* src, void* hip_stream, rosaq_packed_t** out) {
+  if (!out) return fail(ROSAQ_ERR_NULL, "out is NULL");
+  *out = nullptr;
+  if (!src) return fail(ROSAQ_ERR_NULL, "handle is NULL");
+  rosaq_packed* p = nullptr;
+  try {
+    p = new rosaq_packed(*src);
+  } catch (const std::bad_alloc&) { return fail(ROSAQ_ERR_NOMEM, "out of host memory"); }
+  p->d_blob = nullptr;
+  if (!src->host_only) {
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipMalloc(&p->d_blob, src->blob_bytes);
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(p->d_blob, src->d_blob, src->blob_bytes, hipMemcpyDeviceToDevice, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) {
+      set_error(std::string("rosaq_packed_clone: ") + hipGetErrorString(e));
+      if (p->d_blob) (void)hipFree(p->d_blob);
+      delete p;
+      return ROSAQ_ERR_HIP;
+    }
+    const ptrdiff_t shift = static_cast<char*>(p->d_blob) - static_cast<char*>(src->d_blob);
+    auto move = [shift](auto*& q) { q = reinterpret_cast<std::remove_reference_t<decltype(q)>>(
+                                        reinterpret_cast<char*>(q) + shift); };
+    move(p->d_wS); move(p->d_wq); move(p->d_sz); move(p->d_qf); move(p->d_perm); move(p->d_pos);
   }
   *out = p;
   return ROSAQ_OK;

@@ -159,3 +159,19 @@ def test_stream_probe_argument_errors():
     assert call(shared_ptr=0) == -2
     assert call(sink_bytes=1024) == -6
     assert call(src_ptr=S + 4) == -5
+
+
+def test_clone_of_host_only_handle():
+    import ctypes as C
+    W, Q, lam, K, bits, mode = _good(mode=B.Q_HEADWISE)
+    p = B.rosaq_pack_weights(W, Q, lam, K, bits, mode, host_only=True)
+    c = B.rosaq_packed_clone(p)
+    a, b = B.rosaq_packed_export(p), B.rosaq_packed_export(c)
+    p.free()                                        # the clone owns its own copies
+    for k in a:
+        assert np.array_equal(a[k].view(np.uint8), b[k].view(np.uint8)), k
+    assert (c.N, c.D, c.K, c.bits, c.q_mode) == (16, 256, 128, 4, B.Q_HEADWISE)
+    out = C.c_void_p()
+    assert B.lib().rosaq_packed_clone(None, None, C.byref(out)) == -1
+    assert B.lib().rosaq_packed_clone(c.handle, None, None) == -1
+    c.free()

@@ -177,3 +177,20 @@ def test_stream_probe_runs_and_writes_nothing():
                              sink.data_ptr(), sink.numel(), st)
     torch.cuda.synchronize()
     assert bool((sink == 9).all())
+
+
+def test_clone_runs_like_the_original_and_batches_with_it():
+    from paper_2506_13472_amd import torch_glue as T
+    print("case clone", flush=True)
+    lay, Q, lam = make_case(9, 20, 256, 64, 300, O.MODE_HEADWISE)
+    p = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_HEADWISE)
+    c = B.rosaq_packed_clone(p)
+    y0 = run_gpu(p, lay["x"])
+    p.free()
+    y1 = run_gpu(c, lay["x"])
+    assert np.array_equal(y0.view(np.uint16), y1.view(np.uint16))
+    c2 = B.rosaq_packed_clone(c)
+    ys = T.linear_batch([c, c2], torch.from_numpy(lay["x"]).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(ys[1].cpu().numpy().view(np.uint16), y0.view(np.uint16))
+    c.free(); c2.free()
