@@ -79,6 +79,19 @@ struct GemmSeg {
   int N;
   int chunk_end;     // exclusive prefix sum of channel chunks over the layers
 };
+#ifdef ROSAQ_PROBE_TIMELINE
+// probe builds only: per-wave shader-clock stamps of the last launch
+__device__ unsigned long long g_timeline[4096 * 16 * 8];
+#define ROSAQ_STAMP(i)                                                                  \
+  if (lane == 0 && blockIdx.x < 4096)                                                   \
+    g_timeline[(static_cast<size_t>(blockIdx.x) * 16 + wave) * 8 + (i)] = wall_clock64();
+extern "C" int rosaq_debug_timeline(void* host, size_t bytes) {
+  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timeline), bytes, 0, hipMemcpyDeviceToHost));
+}
+#else
+#define ROSAQ_STAMP(i)
+#endif
+
 struct GemmDev {
   const uint4* xf;
   GemmSeg seg[kMaxBatch];
@@ -129,6 +142,7 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
   int chunk = xcd + 8 * (local / p.mgroups);
   const int mg = local % p.mgroups;
   if (chunk >= p.chunks) return;
+  ROSAQ_STAMP(0)
   // which layer of the batch this chunk belongs to (uniform over the workgroup)
   int si = 0;
 #pragma unroll
@@ -274,10 +288,14 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
     for (int d = 0; d < DEPTH; ++d) {
       if (g + d * WPB < G) {
         compute_group(r[d]);
+#ifdef ROSAQ_PROBE_TIMELINE
+        if (d == 0 && g < WPB) { ROSAQ_STAMP(1) }
+#endif
         if (g + (d + DEPTH) * WPB < G) load_group(g + (d + DEPTH) * WPB, r[d]);
       }
     }
   }
+  ROSAQ_STAMP(2)
 
 #ifdef ROSAQ_PROBE_NO_EPI
   {
@@ -299,6 +317,7 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
       red[wave][nt * MT + mt][lane] = make_float4(v[0], v[1], v[2], v[3]);
     }
   __syncthreads();
+  ROSAQ_STAMP(3)
 
   constexpr int kSlots = NT * MT;
   for (int slot = wave; slot < kSlots; slot += WPB) {
@@ -310,6 +329,7 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
     }
     store_fragment(p, sg, v, mtile0 + slot % MT, tile0 + slot / MT, lane);
   }
+  ROSAQ_STAMP(4)
 }
 
 // xhat fragments from x by a column permutation (or identity): the prologue of
