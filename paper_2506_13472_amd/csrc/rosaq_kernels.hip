@@ -171,6 +171,9 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
     const int mtile = mtile0 + mt;
     xa[mt] = p.xf + (static_cast<size_t>(mtile >> 2) * p.KS * 4 + (mtile & 3)) * 64 + lane;
   }
+  // Skinny inputs (single row tile per workgroup): lanes whose row is beyond M skip the
+  // load, so a decode step with a few rows does not pull 16 rows of padding per k-step.
+  const bool row_ok = MT > 1 || mtile0 * 16 + (lane & 15) < p.M;
 
   // Per-wave work list: fp16 k-steps u = wave, wave + WPB, ... and low-bit groups
   // g = g_first, g_first + WPB, ... (unit ks_s + g belongs to wave (ks_s + g) % WPB).
@@ -190,7 +193,8 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
     for (int nt = 0; nt < NT; ++nt)
       r.b[nt] = sg.wS[(static_cast<size_t>(tile0 + nt) * p.ks_s + u) * 64 + lane];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) r.a[mt] = xa[mt][static_cast<size_t>(u) * 256];
+    for (int mt = 0; mt < MT; ++mt)
+      r.a[mt] = row_ok ? xa[mt][static_cast<size_t>(u) * 256] : make_uint4(0, 0, 0, 0);
   };
 #ifdef ROSAQ_PROBE_NO_X
 #define ROSAQ_XLOAD(dst, src) dst = make_uint4(lane, 1, 2, 3)
@@ -227,7 +231,10 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) ROSAQ_XLOAD(r.a[t][mt], xa[mt][(ks0 + t) * 256]);
+      for (int mt = 0; mt < MT; ++mt) {
+        r.a[t][mt] = make_uint4(0, 0, 0, 0);
+        if (row_ok) { ROSAQ_XLOAD(r.a[t][mt], xa[mt][(ks0 + t) * 256]); }
+      }
   };
   auto compute_group = [&](const GroupRegs& r) {
 #ifdef ROSAQ_PROBE_NO_COMPUTE
@@ -475,7 +482,7 @@ GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tu
   if (tune.wpb == 4 && s.mt * s.nt >= 8) s.wpb = 4;     // one wave per SIMD: 512 registers
   // loads in flight per wave: depth 1 variants of the small tiles fit 128 registers,
   // so two workgroups share a CU and cover each other's latency
-  s.depth = (s.mt * s.nt <= 4 || s.mt * s.nt == 16) ? 1 : 2;
+  s.depth = ((s.mt * s.nt <= 4 && s.mt > 1) || s.mt * s.nt == 16) ? 1 : 2;   // skinny tiles: latency, not occupancy
   if (tune.depth >= 1 && tune.depth <= 4) s.depth = tune.depth;
   // deepest prefetch that still fits the register file without spilling
   int max_depth = 4;
