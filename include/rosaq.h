@@ -44,6 +44,19 @@ extern "C" {
 #define ROSAQ_Q_FULL     1
 #define ROSAQ_Q_HEADWISE 2
 
+/* Which rotated channels stay FP16 (ties always go to the lower channel index).
+ * TOP is the method (Sec. 3.2).  TOP_PER_HEAD keeps K / (D/128) channels in every
+ * 128-channel head, the setting the weight-splitting appendix uses for the attention
+ * output projection (32 per head).  The other three are the ablation rules of the
+ * salient-channel appendix: BOTTOM = the K smallest eigenvalues; CONSECUTIVE = channels
+ * select_arg .. select_arg+K-1 (the caller draws the random start); TOP_AND_BOTTOM =
+ * K/2 largest plus K/2 smallest among the rest (total K, so the format is unchanged). */
+#define ROSAQ_SELECT_TOP            0
+#define ROSAQ_SELECT_TOP_PER_HEAD   1
+#define ROSAQ_SELECT_BOTTOM         2
+#define ROSAQ_SELECT_CONSECUTIVE    3
+#define ROSAQ_SELECT_TOP_AND_BOTTOM 4
+
 typedef struct rosaq_packed rosaq_packed_t;   /* opaque; owns its host and device buffers */
 
 /* Description of one linear layer to pack (Sec. 3.1-3.3; Eq. 3).  All pointers HOST;
@@ -62,13 +75,14 @@ typedef struct {
   int32_t K;                 /* number of FP16 salient channels, multiple of 32, (D-K) % 128 == 0 */
   int32_t bits;              /* 3 or 4                                                        */
   int32_t group;             /* 128                                                           */
-  int32_t select_rule;       /* 0 = the K largest eigenvalues (ties: lower channel first)     */
+  int32_t select_rule;       /* ROSAQ_SELECT_* (0 = the K largest eigenvalues, the method)      */
   int32_t host_only;         /* nonzero: build the canonical arrays only, touch no GPU         */
+  int32_t select_arg;        /* first channel for ROSAQ_SELECT_CONSECUTIVE, else ignored       */
 } rosaq_pack_desc;
 
 /* rosaq_pack_weights - offline step of the method (Sec. 3.1-3.3, Eq. 1-3):
  *   1. What = W Q in fp64, rounded once to fp16 (HEADWISE: per 128-column block);
- *   2. salient_idx = the K channels with the largest eigenvalues, ascending;
+ *   2. salient_idx = the K channels picked by select_rule (default: largest eigenvalues), ascending;
  *      storage order perm = [salient_idx ; all other channels ascending];
  *   3. W_S = What[:, salient_idx] kept as fp16;
  *   4. the other columns, in storage order, are cut into groups of 128 and each

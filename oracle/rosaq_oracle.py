@@ -14,7 +14,8 @@ Steps (paper passages they follow):
   pca_full / pca_headwise   Sec. 3.1 Eq. 4 (X^T X = R Lambda R^T, columns sorted
                             by eigenvalue) and Sec. 3.1.1 Eq. 5-6 (one PCA per head)
   rotate_weights            Eq. 1-2 (X W = (X R)(R^T W)), transposed layout
-  select_salient            Sec. 3.2 (channels with the K largest eigenvalues)
+  select_salient            Sec. 3.2 (channels with the K largest eigenvalues); the per-head
+                            setting of the weight-splitting appendix and the ablation rules of App. B
   quantize_groups           Eq. 2, Sec. 3.3, Sec. 4.1 (per-group, 128 channels,
                             INT3/INT4); the formula itself is not in the paper,
                             the reading used is asymmetric min-max round-to-nearest
@@ -227,15 +228,54 @@ def rotate_weights(W16, Q, mode: int):
 # --------------------------------------------------------------------------
 # Sec. 3.2: salient channel identification
 # --------------------------------------------------------------------------
-def select_salient(lam, K: int):
-    """The K rotated channels with the largest eigenvalues (ties -> lower channel
-    index), reported ascending, and the storage permutation
-    perm = [salient ; every other channel ascending]."""
+RULE_TOP = 0            # Sec. 3.2: the K largest eigenvalues (the method)
+RULE_TOP_PER_HEAD = 1   # weight-splitting appendix: the same number of salient channels in every head
+RULE_BOTTOM = 2         # ablation of App. B: the K smallest eigenvalues
+RULE_CONSECUTIVE = 3    # ablation of App. B: K consecutive channels from a given start ("Random")
+RULE_TOP_AND_BOTTOM = 4 # ablation of App. B: K/2 largest and K/2 smallest
+
+
+def select_salient(lam, K: int, rule: int = RULE_TOP, arg: int = 0, head_dim: int = 128):
+    """Salient rotated channels, reported ascending, and the storage permutation
+    perm = [salient ; every other channel ascending].  Ties go to the lower channel.
+
+    TOP            the K largest eigenvalues (Sec. 3.2)
+    TOP_PER_HEAD   K / H largest inside every block of head_dim channels (the paper keeps
+                   32 per head for the attention output projection)
+    BOTTOM         the K smallest eigenvalues
+    CONSECUTIVE    channels arg .. arg + K - 1 (the caller draws the random start)
+    TOP_AND_BOTTOM K/2 largest, then K/2 smallest among the remaining channels
+                   (reading of "takes both": the total stays K so the storage format is unchanged)
+    """
     lam = as_f64(lam)
     D = lam.shape[0]
     assert 0 <= K <= D
-    order = np.argsort(-lam, kind="stable")
-    sal = np.sort(order[:K]).astype(np.int32)
+    desc = np.argsort(-lam, kind="stable")          # largest first, ties: lower index first
+    asc = np.argsort(lam, kind="stable")            # smallest first, ties: lower index first
+    if rule == RULE_TOP:
+        chosen = desc[:K]
+    elif rule == RULE_TOP_PER_HEAD:
+        H = D // head_dim
+        assert D % head_dim == 0 and K % H == 0
+        per = K // H
+        chosen = np.concatenate([h * head_dim + np.argsort(-lam[h * head_dim:(h + 1) * head_dim],
+                                                           kind="stable")[:per] for h in range(H)]) \
+            if K else np.zeros(0, np.int64)
+    elif rule == RULE_BOTTOM:
+        chosen = asc[:K]
+    elif rule == RULE_CONSECUTIVE:
+        assert 0 <= arg <= D - K
+        chosen = np.arange(arg, arg + K)
+    elif rule == RULE_TOP_AND_BOTTOM:
+        assert K % 2 == 0
+        top = desc[:K // 2]
+        taken = np.zeros(D, dtype=bool)
+        taken[top] = True
+        bottom = [c for c in asc if not taken[c]][:K // 2]
+        chosen = np.concatenate([top, np.array(bottom, dtype=np.int64)])
+    else:
+        raise ValueError(rule)
+    sal = np.sort(chosen).astype(np.int32)
     mask = np.ones(D, dtype=bool)
     mask[sal] = False
     rest = np.nonzero(mask)[0].astype(np.int32)
@@ -285,7 +325,8 @@ def dequantize_groups(codes, scales, zeros, group: int = 128) -> np.ndarray:
 # --------------------------------------------------------------------------
 # Eq. 3: the stored mixed-precision layer
 # --------------------------------------------------------------------------
-def pack(W16, Q, lam, K: int, bits: int, mode: int, group: int = 128) -> dict:
+def pack(W16, Q, lam, K: int, bits: int, mode: int, group: int = 128, rule: int = RULE_TOP,
+         arg: int = 0) -> dict:
     """Offline steps for one linear: rotate (Eq. 1), pick salient channels
     (Sec. 3.2), keep them in fp16 and quantise the rest group by group in
     storage order (Eq. 3, Sec. 3.3)."""
@@ -293,7 +334,7 @@ def pack(W16, Q, lam, K: int, bits: int, mode: int, group: int = 128) -> dict:
     N, D = W16.shape
     assert (D - K) % group == 0
     What, What16 = rotate_weights(W16, Q, mode)
-    sal, perm = select_salient(lam, K)
+    sal, perm = select_salient(lam, K, rule, arg)
     W_S = What16[:, sal].copy()
     W_N = What16[:, perm[K:]]
     if D > K:

@@ -56,7 +56,8 @@ static int check_desc(const rosaq_pack_desc* d) {
   if (d->group != kGroup) return fail(ROSAQ_ERR_ARG, "group must be 128");
   if (d->q_mode == ROSAQ_Q_HEADWISE && d->head_dim != kHeadDim)
     return fail(ROSAQ_ERR_ARG, "head_dim must be 128");
-  if (d->select_rule != 0) return fail(ROSAQ_ERR_ARG, "select_rule must be 0");
+  if (d->select_rule < ROSAQ_SELECT_TOP || d->select_rule > ROSAQ_SELECT_TOP_AND_BOTTOM)
+    return fail(ROSAQ_ERR_ARG, "select_rule is not one of ROSAQ_SELECT_*");
   if (d->out_features < 1 || d->in_features < 1)
     return fail(ROSAQ_ERR_SHAPE, "out_features and in_features must be positive");
   if (d->in_features % 128 != 0) return fail(ROSAQ_ERR_SHAPE, "in_features must be a multiple of 128");
@@ -65,6 +66,13 @@ static int check_desc(const rosaq_pack_desc* d) {
   if ((d->in_features - d->K) % d->group != 0)
     return fail(ROSAQ_ERR_SHAPE, "in_features - K must be a multiple of group");
   if (d->ldw < d->in_features) return fail(ROSAQ_ERR_SHAPE, "ldw is smaller than in_features");
+  if (d->select_rule == ROSAQ_SELECT_TOP_PER_HEAD && d->K % (d->in_features / kHeadDim) != 0)
+    return fail(ROSAQ_ERR_SHAPE, "K must be a multiple of the number of 128-channel heads");
+  if (d->select_rule == ROSAQ_SELECT_TOP_AND_BOTTOM && d->K % 2 != 0)
+    return fail(ROSAQ_ERR_SHAPE, "K must be even for TOP_AND_BOTTOM");
+  if (d->select_rule == ROSAQ_SELECT_CONSECUTIVE &&
+      (d->select_arg < 0 || d->select_arg > d->in_features - d->K))
+    return fail(ROSAQ_ERR_SHAPE, "select_arg must lie in [0, in_features - K]");
   return ROSAQ_OK;
 }
 

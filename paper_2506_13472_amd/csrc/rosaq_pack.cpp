@@ -166,13 +166,50 @@ int pack_host(const rosaq_pack_desc& d, Canonical* c, std::string* err) {
     if (bad) { *err = "rotated weight overflows fp16"; return ROSAQ_ERR_NONFINITE; }
   }
 
-  // 2. salient channels: K largest eigenvalues, ties to the lower channel (Sec. 3.2)
-  std::vector<int32_t> order(D);
-  std::iota(order.begin(), order.end(), 0);
-  std::stable_sort(order.begin(), order.end(),
-                   [&](int a, int b) { return d.eigenvalues[a] > d.eigenvalues[b]; });
+  // 2. salient channels (Sec. 3.2; per-head and ablation rules of the appendices).
+  //    Every rule ranks channels by eigenvalue with ties going to the lower channel.
   std::vector<char> is_sal(D, 0);
-  for (int i = 0; i < K; ++i) is_sal[order[i]] = 1;
+  {
+    const double* lam = d.eigenvalues;
+    auto ranked = [&](int lo, int hi, bool largest_first) {
+      std::vector<int32_t> idx(hi - lo);
+      std::iota(idx.begin(), idx.end(), lo);
+      std::stable_sort(idx.begin(), idx.end(), [&](int a, int b) {
+        return largest_first ? lam[a] > lam[b] : lam[a] < lam[b];
+      });
+      return idx;
+    };
+    switch (d.select_rule) {
+      case ROSAQ_SELECT_TOP_PER_HEAD: {
+        const int H = D / kHeadDim, per = K / H;
+        for (int h = 0; h < H; ++h) {
+          const std::vector<int32_t> r = ranked(h * kHeadDim, (h + 1) * kHeadDim, true);
+          for (int i = 0; i < per; ++i) is_sal[r[i]] = 1;
+        }
+        break;
+      }
+      case ROSAQ_SELECT_BOTTOM: {
+        const std::vector<int32_t> r = ranked(0, D, false);
+        for (int i = 0; i < K; ++i) is_sal[r[i]] = 1;
+        break;
+      }
+      case ROSAQ_SELECT_CONSECUTIVE:
+        for (int i = 0; i < K; ++i) is_sal[d.select_arg + i] = 1;
+        break;
+      case ROSAQ_SELECT_TOP_AND_BOTTOM: {
+        const std::vector<int32_t> top = ranked(0, D, true), bottom = ranked(0, D, false);
+        for (int i = 0; i < K / 2; ++i) is_sal[top[i]] = 1;
+        int taken = 0;
+        for (int i = 0; i < D && taken < K / 2; ++i)
+          if (!is_sal[bottom[i]]) { is_sal[bottom[i]] = 2; ++taken; }
+        break;
+      }
+      default: {
+        const std::vector<int32_t> r = ranked(0, D, true);
+        for (int i = 0; i < K; ++i) is_sal[r[i]] = 1;
+      }
+    }
+  }
   c->salient_idx.clear(); c->perm.clear();
   for (int ch = 0; ch < D; ++ch) if (is_sal[ch]) c->salient_idx.push_back(ch);
   c->perm = c->salient_idx;

@@ -49,7 +49,11 @@ def test_pack_argument_errors():
     assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, K, 5, mode, host_only=True)) == -3
     assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, K, bits, mode, group=64, host_only=True)) == -3
     assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, K, bits, 7, host_only=True)) == -3
-    assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, K, bits, mode, select_rule=3, host_only=True)) == -3
+    assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, K, bits, mode, select_rule=7, host_only=True)) == -3
+    assert _code(lambda: B.rosaq_pack_weights(W, Q, lam, K, bits, mode, select_rule=3, select_arg=200,
+                                              host_only=True)) == -2
+    assert _code(lambda: B.rosaq_pack_weights(np.zeros((16, 384), np.float16), None, np.arange(384.0), 128, bits, mode,
+                                              select_rule=1, host_only=True)) == -2   # 128 % 3 heads
     Wh, Qh, lamh, *_ = _good(mode=B.Q_HEADWISE)
     assert _code(lambda: B.rosaq_pack_weights(Wh, Qh, lamh, K, bits, B.Q_HEADWISE, head_dim=64,
                                               host_only=True)) == -3

@@ -194,3 +194,17 @@ def test_clone_runs_like_the_original_and_batches_with_it():
     torch.cuda.synchronize()
     assert np.array_equal(ys[1].cpu().numpy().view(np.uint16), y0.view(np.uint16))
     c.free(); c2.free()
+
+
+@pytest.mark.parametrize("rule,arg,K", [(B.SELECT_TOP_PER_HEAD, 0, 128), (B.SELECT_CONSECUTIVE, 200, 128),
+                                        (B.SELECT_TOP_AND_BOTTOM, 0, 128), (B.SELECT_BOTTOM, 0, 128)])
+def test_selection_rules_on_gpu(rule, arg, K):
+    """Paper's per-head setting (32 salient channels per head at K = 128, 4 heads) and the
+    ablation rules: other storage orders through the same kernels."""
+    print(f"case select rule={rule} arg={arg} K={K}", flush=True)
+    lay, Q, lam = make_case(33, 48, 512, 160, 400, O.MODE_HEADWISE)
+    ref = O.pack(lay["W"], Q, lam, K, 4, O.MODE_HEADWISE, rule=rule, arg=arg)
+    p = B.rosaq_pack_weights(lay["W"], Q, lam, K, 4, B.Q_HEADWISE, select_rule=rule, select_arg=arg)
+    check_pack(p, ref)
+    check_output(run_gpu(p, lay["x"]), lay["x"], Q, ref)
+    p.free()

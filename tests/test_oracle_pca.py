@@ -128,3 +128,48 @@ def test_top_rotated_channel_dominates():
     rot = np.abs(lay["X_cal"] @ Q).mean(axis=0)
     orig = np.abs(lay["X_cal"]).mean(axis=0)
     assert np.argmax(rot) == 0 and rot[0] >= orig.max()
+
+
+def test_selection_rules_by_definition():
+    rng = np.random.default_rng(11)
+    D, K, hd = 256, 64, 128
+    lam = rng.random(D)
+    lam[5] = lam[200] = lam.max()                       # ties
+    lam[7] = lam[130] = lam.min()
+    rank_desc = sorted(range(D), key=lambda c: (-lam[c], c))
+    rank_asc = sorted(range(D), key=lambda c: (lam[c], c))
+    sal, perm = O.select_salient(lam, K, O.RULE_BOTTOM)
+    assert sal.tolist() == sorted(rank_asc[:K])
+    sal, _ = O.select_salient(lam, K, O.RULE_CONSECUTIVE, arg=37)
+    assert sal.tolist() == list(range(37, 37 + K))
+    sal, _ = O.select_salient(lam, K, O.RULE_TOP_AND_BOTTOM)
+    top = rank_desc[:K // 2]
+    bottom = [c for c in rank_asc if c not in top][:K // 2]
+    assert sal.tolist() == sorted(top + bottom) and len(set(sal.tolist())) == K
+    sal, perm = O.select_salient(lam, K, O.RULE_TOP_PER_HEAD, head_dim=hd)
+    for h in range(D // hd):
+        want = sorted(sorted(range(h * hd, (h + 1) * hd), key=lambda c: (-lam[c], c))[:K // 2])
+        assert sal[(sal >= h * hd) & (sal < (h + 1) * hd)].tolist() == want
+    assert sorted(perm.tolist()) == list(range(D)) and perm[:K].tolist() == sal.tolist()
+    # all-equal spectrum: halves of TOP_AND_BOTTOM stay disjoint
+    sal, _ = O.select_salient(np.ones(16), 8, O.RULE_TOP_AND_BOTTOM)
+    assert sal.tolist() == list(range(8))
+    # sorted-within-head spectrum (what head-wise PCA gives): per-head rule = prefix of each head
+    lam2 = np.concatenate([np.sort(rng.random(hd))[::-1] for _ in range(2)])
+    sal, _ = O.select_salient(lam2, 64, O.RULE_TOP_PER_HEAD, head_dim=hd)
+    assert sal.tolist() == list(range(32)) + list(range(128, 160))
+
+
+def test_top_rule_beats_the_ablation_rules_on_output_error():
+    # synthetic analogue of the paper's salient-channel ablation: keeping the top-eigenvalue
+    # channels in fp16 gives a smaller output error than bottom / a consecutive block elsewhere
+    lay = synth.make_layer(3, 32, 256, 48, 512)
+    Q, lam = O.pca_full(lay["X_cal"], "jacobi")
+    Q32 = Q.astype(np.float32)
+    err = {}
+    for name, rule, arg in (("top", O.RULE_TOP, 0), ("bottom", O.RULE_BOTTOM, 0),
+                            ("block", O.RULE_CONSECUTIVE, 100), ("both", O.RULE_TOP_AND_BOTTOM, 0)):
+        p = O.pack(lay["W"], Q32, lam, 128, 3, O.MODE_FULL, rule=rule, arg=arg)
+        err[name] = O.quality_report(lay["x"], lay["W"], Q32, p)
+    assert err["top"] < err["bottom"] and err["top"] < err["block"]
+    assert err["top"] < err["both"] < err["bottom"]       # the ordering of the paper's ablation table

@@ -106,3 +106,19 @@ def test_f16_conversion_of_rotated_weights_covers_subnormals_and_ties():
         ref = O.pack(W, Q, lam, D, 4, O.MODE_FULL)
         p = B.rosaq_pack_weights(W, Q, lam, D, 4, B.Q_FULL, host_only=True)
         _compare(p, ref)
+
+
+@pytest.mark.parametrize("rule,arg,K", [(B.SELECT_TOP_PER_HEAD, 0, 128), (B.SELECT_BOTTOM, 0, 128),
+                                        (B.SELECT_CONSECUTIVE, 77, 128), (B.SELECT_TOP_AND_BOTTOM, 0, 128),
+                                        (B.SELECT_TOP_PER_HEAD, 0, 256)])
+def test_selection_rules_bit_exact(rule, arg, K):
+    lay = synth.make_layer(5, 4, 512, 40, 512)
+    Qb, lam = O.pca_headwise(lay["X_cal"], 128, "jacobi")
+    Qb32 = Qb.astype(np.float32)
+    ref = O.pack(lay["W"], Qb32, lam, K, 4, O.MODE_HEADWISE, rule=rule, arg=arg)
+    p = B.rosaq_pack_weights(lay["W"], Qb32, lam, K, 4, B.Q_HEADWISE, host_only=True,
+                             select_rule=rule, select_arg=arg)
+    _compare(p, ref)
+    if rule == B.SELECT_TOP_PER_HEAD:
+        sal = B.rosaq_packed_export(p)["salient_idx"]
+        assert [int(np.sum((sal >= 128 * h) & (sal < 128 * (h + 1)))) for h in range(4)] == [K // 4] * 4
