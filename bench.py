@@ -368,6 +368,12 @@ def main():
         probe["weights_only_GBps"] = round(pb / (probe["weights_only_us"] * 1e-6) / 1e9, 1)
         del srcs
 
+    # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE (x 2.0 by a 256 MiB copy)
+    # + WRITE_SIZE (x 1.0), profiles/gemm_kernel_llama7b_attn_M64_int4.md: one 4096 x 4096 launch moves
+    # 13.96 MB + 0.52 MB, a q/k/v launch 33.37 MB + 1.57 MB; the default step averages the two.
+    one, qkv3 = 13635 * 1024 + 512 * 1024, 32592 * 1024 + 1536 * 1024
+    traffic = {None: (one + qkv3) // 2, "qkv": qkv3, "o": one}[args.only] if not args.unbatched else one
+
     out = {
         "metric": "fused ROSAQ linear HBM GB/s at M=64 (algorithmic bytes / time)",
         "value": round(gbs, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -390,7 +396,7 @@ def main():
         "stream_probe": probe,
         "roofline": {"kernel": "gemm_kernel", "bound": "hbm", "achieved": round(gemm_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None, "bytes_per_launch": gemm_bytes, "launches_per_step": launches // args.steps,
+                     "traffic": traffic, "bytes_per_launch": gemm_bytes, "launches_per_step": launches // args.steps,
                      "us_per_launch": round(us_gemm, 3)},
     }
     if not args.no_cpu_baseline:

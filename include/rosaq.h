@@ -78,6 +78,11 @@ typedef struct {
   int32_t select_rule;       /* ROSAQ_SELECT_* (0 = the K largest eigenvalues, the method)      */
   int32_t host_only;         /* nonzero: build the canonical arrays only, touch no GPU         */
   int32_t select_arg;        /* first channel for ROSAQ_SELECT_CONSECUTIVE, else ignored       */
+  int32_t rotation_absorbed; /* nonzero: W is rotated by Q at pack time as usual, but the caller */
+                             /* feeds already-rotated activations (the rotation was folded into  */
+                             /* the producing layer offline, as the paper deploys it): at run    */
+                             /* time the handle behaves as q_mode NONE and is served by          */
+                             /* rosaq_linear with x = xhat                                       */
 } rosaq_pack_desc;
 
 /* rosaq_pack_weights - offline step of the method (Sec. 3.1-3.3, Eq. 1-3):

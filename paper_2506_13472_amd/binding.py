@@ -32,7 +32,8 @@ class PackDesc(C.Structure):
                 ("q_mode", C.c_int32), ("head_dim", C.c_int32),
                 ("Q", C.c_void_p), ("eigenvalues", C.c_void_p),
                 ("K", C.c_int32), ("bits", C.c_int32), ("group", C.c_int32),
-                ("select_rule", C.c_int32), ("host_only", C.c_int32), ("select_arg", C.c_int32)]
+                ("select_rule", C.c_int32), ("host_only", C.c_int32), ("select_arg", C.c_int32),
+                ("rotation_absorbed", C.c_int32)]
 
 
 class RosaqError(RuntimeError):
@@ -123,7 +124,7 @@ class Packed:
 
 
 def rosaq_pack_weights(W: np.ndarray, Q, eigenvalues: np.ndarray, K: int, bits: int, q_mode: int,
-                       group: int = 128, head_dim: int = 128, select_rule: int = 0, select_arg: int = 0,
+                       group: int = 128, head_dim: int = 128, select_rule: int = 0, select_arg: int = 0, rotation_absorbed: bool = False,
                        host_only: bool = False, stream: int = 0, ldw: int | None = None,
                        out_features: int | None = None, in_features: int | None = None) -> Packed:
     """W fp16 [N, D]; Q fp32 ([D, D] or [H, 128, 128]) or None; eigenvalues fp64 [D]."""
@@ -139,6 +140,7 @@ def rosaq_pack_weights(W: np.ndarray, Q, eigenvalues: np.ndarray, K: int, bits: 
     d.Q, d.eigenvalues = _ptr(Qc), _ptr(lam)
     d.K, d.bits, d.group, d.select_rule, d.host_only = K, bits, group, select_rule, int(host_only)
     d.select_arg = select_arg
+    d.rotation_absorbed = int(rotation_absorbed)
     out = C.c_void_p()
     _check(lib().rosaq_pack_weights(C.byref(d), C.c_void_p(stream), C.byref(out)))
     return Packed(out.value)

@@ -232,6 +232,7 @@ int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_pack
       h = fnv1a(h, desc->Q, sizeof(float) * desc->in_features * static_cast<size_t>(kHeadDim));
     p->rot_fingerprint = h;
   }
+  if (desc->rotation_absorbed) p->c.q_mode = ROSAQ_Q_NONE;   // run time sees rotated activations
   if (!desc->host_only) {
     rc = upload(p, desc->Q, static_cast<hipStream_t>(hip_stream));
     if (rc != ROSAQ_OK) { rosaq_free(p); return rc; }

@@ -208,3 +208,19 @@ def test_selection_rules_on_gpu(rule, arg, K):
     check_pack(p, ref)
     check_output(run_gpu(p, lay["x"]), lay["x"], Q, ref)
     p.free()
+
+
+def test_rotation_absorbed_offline_per_head_salient():
+    """The paper's own deployment of the attention output projection: 32 salient channels per
+    head, rotation folded into the producer, so the layer receives rotated activations."""
+    print("case absorbed", flush=True)
+    lay, Q, lam = make_case(35, 64, 512, 192, 400, O.MODE_HEADWISE)
+    ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_HEADWISE, rule=O.RULE_TOP_PER_HEAD)
+    p = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_HEADWISE, select_rule=B.SELECT_TOP_PER_HEAD,
+                             rotation_absorbed=True)
+    assert p.q_mode == B.Q_NONE
+    check_pack(p, ref)
+    xhat16 = O.fp16_rne(O.rotate(lay["x"], O.round_rotation(Q, O.MODE_HEADWISE), O.MODE_HEADWISE))
+    ref_rt = dict(ref); ref_rt["mode"] = O.MODE_NONE          # same stored layer, no run-time rotation
+    check_output(run_gpu(p, xhat16), xhat16, None, ref_rt)
+    p.free()

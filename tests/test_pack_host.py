@@ -122,3 +122,14 @@ def test_selection_rules_bit_exact(rule, arg, K):
     if rule == B.SELECT_TOP_PER_HEAD:
         sal = B.rosaq_packed_export(p)["salient_idx"]
         assert [int(np.sum((sal >= 128 * h) & (sal < 128 * (h + 1)))) for h in range(4)] == [K // 4] * 4
+
+
+def test_rotation_absorbed_packs_the_same_arrays():
+    lay = synth.make_layer(6, 4, 256, 24, 300)
+    Qb, lam = O.pca_headwise(lay["X_cal"], 128, "jacobi")
+    Qb32 = Qb.astype(np.float32)
+    ref = O.pack(lay["W"], Qb32, lam, 128, 4, O.MODE_HEADWISE)
+    p = B.rosaq_pack_weights(lay["W"], Qb32, lam, 128, 4, B.Q_HEADWISE, host_only=True,
+                             rotation_absorbed=True)
+    _compare(p, ref)
+    assert p.q_mode == B.Q_NONE
