@@ -85,6 +85,40 @@ static int check_desc(const rosaq_pack_desc* d) {
     }                                                                           \
   } while (0)
 
+// What = fp16(W Q) for a dense rotation on the GPU (fp64 FMA chain per output): the host
+// version of the same product takes tens of seconds at D >= 4096.
+static int rotate_on_device(const rosaq_pack_desc& d, hipStream_t st, std::vector<uint16_t>* out) {
+  const size_t N = d.out_features, D = d.in_features;
+  void *dW = nullptr, *dQ = nullptr, *dO = nullptr;
+  std::vector<uint16_t> wc;
+  const uint16_t* wsrc = d.W;
+  if (d.ldw != static_cast<int64_t>(D)) {
+    wc.resize(N * D);
+    for (size_t n = 0; n < N; ++n) std::memcpy(&wc[n * D], d.W + n * d.ldw, D * 2);
+    wsrc = wc.data();
+  }
+  out->resize(N * D);
+  hipError_t e = hipMalloc(&dW, N * D * 2);
+  if (e == hipSuccess) e = hipMalloc(&dQ, D * D * 4);
+  if (e == hipSuccess) e = hipMalloc(&dO, N * D * 2);
+  if (e == hipSuccess) e = hipMemcpyAsync(dW, wsrc, N * D * 2, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess) e = hipMemcpyAsync(dQ, d.Q, D * D * 4, hipMemcpyHostToDevice, st);
+  int rc = ROSAQ_OK;
+  if (e == hipSuccess) rc = launch_rotate_weights_f64(dW, dQ, dO, static_cast<int>(N), static_cast<int>(D), st);
+  if (e == hipSuccess && rc == ROSAQ_OK)
+    e = hipMemcpyAsync(out->data(), dO, N * D * 2, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess && rc == ROSAQ_OK) e = hipStreamSynchronize(st);
+  if (dW) (void)hipFree(dW);
+  if (dQ) (void)hipFree(dQ);
+  if (dO) (void)hipFree(dO);
+  if (rc != ROSAQ_OK) return rc;
+  if (e != hipSuccess) {
+    set_error(std::string("device rotation: ") + hipGetErrorString(e));
+    return ROSAQ_ERR_HIP;
+  }
+  return ROSAQ_OK;
+}
+
 static int upload(rosaq_packed* p, const float* Q, hipStream_t st) {
   DeviceImage img;
   try {
@@ -220,7 +254,14 @@ int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_pack
   if (!p) return fail(ROSAQ_ERR_NOMEM, "out of host memory");
   std::string err;
   try {
-    rc = pack_host(*desc, &p->c, &err);
+    std::vector<uint16_t> rotated;
+    const bool on_device = !desc->host_only && desc->q_mode == ROSAQ_Q_FULL && desc->in_features >= 1024;
+    if (on_device) {
+      // the packer validates Q and W before it uses the rotated matrix
+      rc = rotate_on_device(*desc, static_cast<hipStream_t>(hip_stream), &rotated);
+      if (rc != ROSAQ_OK) { delete p; return rc; }
+    }
+    rc = pack_host(*desc, &p->c, &err, on_device ? &rotated : nullptr);
   } catch (const std::bad_alloc&) { rc = ROSAQ_ERR_NOMEM; err = "out of host memory"; }
   if (rc != ROSAQ_OK) { delete p; return fail(rc, err); }
   {

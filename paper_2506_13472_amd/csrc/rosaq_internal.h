@@ -33,7 +33,9 @@ struct Canonical {
 };
 
 // Sec. 3.1-3.3 on the host.  Returns ROSAQ_OK or an error code with `err` filled.
-int pack_host(const rosaq_pack_desc& d, Canonical* out, std::string* err);
+// `rotated16` (optional): What = fp16(W Q) [N x D] already computed elsewhere (the device path).
+int pack_host(const rosaq_pack_desc& d, Canonical* out, std::string* err,
+              const std::vector<uint16_t>* rotated16 = nullptr);
 
 // Device images (host staging copies) in the kernels' fragment order.
 struct DeviceImage {
@@ -76,6 +78,8 @@ int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_
 int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void* qh,
                            const int32_t* pos_dev, void* xf, void* stream);
 
+int launch_rotate_weights_f64(const void* W_dev, const void* Q_dev, void* out_dev, int N, int D,
+                              void* stream);
 int launch_stream_probe(const void* src, const void* shared, int workgroups, int threads, int w_kib,
                         int x_kib, int shared_kib, void* sink, void* stream);
 

@@ -437,6 +437,67 @@ __global__ __launch_bounds__(1024) void stream_probe_kernel(const uint4* __restr
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345678u) sink[gw * 64 + lane] = acc;
 }
 
+// ---- offline step on the device: What = W Q in fp64, one rounding to fp16 (Eq. 1) -----
+// fp64 -> fp16 with a single round-half-to-even step: scale so that the fp16 ulp is 1
+// (exact power-of-two scaling), round to integer, reassemble the bit pattern.
+__device__ __forceinline__ uint16_t f64_to_f16_bits(double v) {
+  const uint16_t sign = v < 0.0 || (v == 0.0 && __builtin_signbit(v)) ? 0x8000u : 0u;
+  if (v != v) return 0x7e00u;
+  const double a = __builtin_fabs(v);
+  if (a >= 65520.0) return sign | 0x7c00u;
+  if (a < 6.103515625e-05) {                      // below 2^-14: subnormal grid, ulp 2^-24
+    return sign | static_cast<uint16_t>(__builtin_rint(__builtin_ldexp(a, 24)));
+  }
+  int e;
+  (void)__builtin_frexp(a, &e);                   // a = f * 2^e, f in [0.5, 1)
+  e -= 1;
+  double m = __builtin_rint(__builtin_ldexp(a, 10 - e));   // in [1024, 2048]
+  if (m >= 2048.0) { m = 1024.0; e += 1; }
+  return sign | static_cast<uint16_t>(((e + 15) << 10) + (static_cast<int>(m) - 1024));
+}
+
+// out[n][c] = fp16( sum_k W[n][k] * Q[k][c] ), W fp16 [N x D], Q fp32 [D x D], fp64 FMA chain
+// in increasing k.  64 x 64 outputs per workgroup, 4 x 4 per thread, 16-deep LDS tiles.
+__global__ __launch_bounds__(256) void rotate_weights_f64_kernel(const _Float16* __restrict__ W,
+                                                                 const float* __restrict__ Q,
+                                                                 uint16_t* __restrict__ out, int N,
+                                                                 int D) {
+  __shared__ double sa[16][64 + 1];   // [k][row]
+  __shared__ double sb[16][64];       // [k][col]
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int n0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  double acc[4][4] = {};
+  for (int k0 = 0; k0 < D; k0 += 16) {
+    for (int i = threadIdx.x; i < 64 * 16; i += 256) {
+      const int r = i >> 4, k = i & 15;
+      const int n = n0 + r;
+      sa[k][r] = n < N ? static_cast<double>(W[static_cast<size_t>(n) * D + k0 + k]) : 0.0;
+      const int kk = i >> 6, c = i & 63;
+      sb[kk][c] = static_cast<double>(Q[static_cast<size_t>(k0 + kk) * D + c0 + c]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      double a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = sa[k][ty * 4 + i]; b[i] = sb[k][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fma(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int n = n0 + ty * 4 + i;
+    if (n >= N) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      out[static_cast<size_t>(n) * D + c0 + tx * 4 + j] = f64_to_f16_bits(acc[i][j]);
+  }
+}
+
 // ---- launchers ------------------------------------------------------------------
 static int hip_fail(hipError_t e, const char* what) {
   set_error(std::string(what) + ": " + hipGetErrorString(e));
@@ -545,6 +606,15 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
 #undef ROSAQ_CASE
   set_error("no kernel for this bits / tile combination");
   return ROSAQ_ERR_ARG;
+}
+
+int launch_rotate_weights_f64(const void* W_dev, const void* Q_dev, void* out_dev, int N, int D,
+                              void* stream) {
+  hipLaunchKernelGGL(rotate_weights_f64_kernel, dim3(D / 64, (N + 63) / 64), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const _Float16*>(W_dev),
+                     static_cast<const float*>(Q_dev), static_cast<uint16_t*>(out_dev), N, D);
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "rotate_weights_f64_kernel launch");
 }
 
 int launch_stream_probe(const void* src, const void* shared, int workgroups, int threads, int w_kib,

@@ -125,7 +125,8 @@ void rotate_headwise(const rosaq_pack_desc& d, std::vector<double>* out) {
 
 }  // namespace
 
-int pack_host(const rosaq_pack_desc& d, Canonical* c, std::string* err) {
+int pack_host(const rosaq_pack_desc& d, Canonical* c, std::string* err,
+              const std::vector<uint16_t>* rotated16) {
   const int N = d.out_features, D = d.in_features, K = d.K;
   c->N = N; c->D = D; c->K = K; c->bits = d.bits; c->q_mode = d.q_mode;
   c->G = (D - K) / kGroup;
@@ -146,10 +147,15 @@ int pack_host(const rosaq_pack_desc& d, Canonical* c, std::string* err) {
   }
 
   // 1. rotate, round once to fp16
-  std::vector<uint16_t> what(static_cast<size_t>(N) * D);
-  if (d.q_mode == ROSAQ_Q_NONE) {
+  std::vector<uint16_t> what_local;
+  if (rotated16 == nullptr) what_local.resize(static_cast<size_t>(N) * D);
+  std::vector<uint16_t>& what_rw = what_local;
+  if (rotated16 != nullptr) {
+    for (uint16_t h : *rotated16)
+      if (((h >> 10) & 31) == 31) { *err = "rotated weight overflows fp16"; return ROSAQ_ERR_NONFINITE; }
+  } else if (d.q_mode == ROSAQ_Q_NONE) {
     for (int n = 0; n < N; ++n)
-      std::memcpy(&what[static_cast<size_t>(n) * D], d.W + static_cast<size_t>(n) * d.ldw,
+      std::memcpy(&what_rw[static_cast<size_t>(n) * D], d.W + static_cast<size_t>(n) * d.ldw,
                   sizeof(uint16_t) * D);
   } else {
     std::vector<double> rot;
@@ -159,12 +165,13 @@ int pack_host(const rosaq_pack_desc& d, Canonical* c, std::string* err) {
     bool bad = false;
     parallel_rows(N, [&](int lo, int hi) {
       for (size_t i = static_cast<size_t>(lo) * D; i < static_cast<size_t>(hi) * D; ++i) {
-        what[i] = f64_to_f16(rot[i]);
-        if (((what[i] >> 10) & 31) == 31) bad = true;
+        what_rw[i] = f64_to_f16(rot[i]);
+        if (((what_rw[i] >> 10) & 31) == 31) bad = true;
       }
     });
     if (bad) { *err = "rotated weight overflows fp16"; return ROSAQ_ERR_NONFINITE; }
   }
+  const std::vector<uint16_t>& what = rotated16 ? *rotated16 : what_local;
 
   // 2. salient channels (Sec. 3.2; per-head and ablation rules of the appendices).
   //    Every rule ranks channels by eigenvalue with ties going to the lower channel.

@@ -224,3 +224,16 @@ def test_rotation_absorbed_offline_per_head_salient():
     ref_rt = dict(ref); ref_rt["mode"] = O.MODE_NONE          # same stored layer, no run-time rotation
     check_output(run_gpu(p, xhat16), xhat16, None, ref_rt)
     p.free()
+
+
+def test_device_rotation_packs_the_same_bits_as_the_host_path():
+    """Dense rotations of D >= 1024 are multiplied into the weight on the GPU (fp64 FMA chain, one
+    rounding to fp16); the host path and the oracle must give the same stored arrays."""
+    print("case device rotation", flush=True)
+    lay, Q, lam = make_case(0, 4, 1024, 300, 64, O.MODE_FULL)
+    ref = O.pack(lay["W"], Q, lam, 128, 3, O.MODE_FULL)
+    p_dev = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 3, B.Q_FULL)
+    p_host = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 3, B.Q_FULL, host_only=True)
+    check_pack(p_dev, ref)
+    check_pack(p_host, ref)
+    p_dev.free(); p_host.free()
