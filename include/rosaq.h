@@ -160,6 +160,19 @@ int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* 
 int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t* W_S,
                         uint8_t* codes, uint16_t* scales, uint16_t* zeros);
 
+/* rosaq_pca_headwise - calibration step of the method on the GPU (Sec. 3.1 Eq. 4 applied per
+ * attention head, Sec. 3.1.1): for every block of 128 input channels the uncentred second
+ * moment C_h = X_h^T X_h / n_cal is accumulated in fp64 and diagonalised by cyclic Jacobi
+ * rotations (off-diagonal norm <= 1e-13 ||C_h||_F).  Results, ready for rosaq_pack_weights:
+ *   Q_host            HOST fp32 [D/128][128][128], eigenvectors as columns, sorted by eigenvalue
+ *                     (descending; each column signed so that its largest entry is positive)
+ *   eigenvalues_host  HOST fp64 [D], descending inside every head, negative round-off clamped to 0
+ *   X_dev             DEVICE fp16 [n_cal x D] calibration activations, row r at X + r*ldx
+ * Allocates its own device scratch and waits for the result (calibration time, not the hot path).
+ * Errors: NULL, SHAPE, ALIGN, HIP, NONFINITE (no convergence within 60 sweeps). */
+int rosaq_pca_headwise(const void* X_dev, int32_t n_cal, int32_t D, int64_t ldx, float* Q_host,
+                       double* eigenvalues_host, void* hip_stream);
+
 /* rosaq_stream_probe - measurement aid, no arithmetic of the method: one launch of
  * `workgroups` x `threads` in which every wave reads its own contiguous share of
  * src_dev (src_bytes in total, 1 KiB per load) and every workgroup then reads

@@ -83,6 +83,9 @@ int launch_rotate_weights_f64(const void* W_dev, const void* Q_dev, void* out_de
 int launch_stream_probe(const void* src, const void* shared, int workgroups, int threads, int w_kib,
                         int x_kib, int shared_kib, void* sink, void* stream);
 
+int pca_headwise_device(const void* X_dev, int n_cal, int D, int64_t ldx, float* Q_host,
+                        double* eig_host, void* stream);
+
 void set_error(const std::string& s);
 
 }  // namespace rosaq

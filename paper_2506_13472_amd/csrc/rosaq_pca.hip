@@ -1,0 +1,220 @@
+// Head-wise PCA on the GPU (Sec. 3.1 Eq. 4, Sec. 3.1.1): per 128-channel head the
+// uncentred second moment C_h = X_h^T X_h / n_cal in fp64 and its eigen-decomposition by
+// cyclic Jacobi rotations, one workgroup per head with the 128 x 128 matrix in LDS.
+// Calibration-time code: it allocates its own scratch and waits for the result.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <numeric>
+#include <vector>
+
+#include "rosaq_internal.h"
+
+namespace rosaq {
+
+constexpr int kH = 128;        // head dimension
+constexpr int kLd = kH + 1;    // padded LDS row stride (doubles): column walks hit distinct banks
+
+// C_h[i][j] = sum_r X[r][h*128+i] * X[r][h*128+j] / n_cal, rows added in increasing r.
+// One workgroup per head, thread t owns the 8 x 8 block (t / 16, t % 16).
+__global__ __launch_bounds__(256) void second_moment_kernel(const _Float16* __restrict__ X,
+                                                            int64_t ldx, int n_cal,
+                                                            double* __restrict__ C) {
+  __shared__ double row[kH];
+  const int h = blockIdx.x;
+  const int bi = (threadIdx.x >> 4) * 8, bj = (threadIdx.x & 15) * 8;
+  double acc[8][8] = {};
+  for (int r = 0; r < n_cal; ++r) {
+    __syncthreads();
+    if (threadIdx.x < kH)
+      row[threadIdx.x] = static_cast<double>(X[static_cast<int64_t>(r) * ldx + h * kH + threadIdx.x]);
+    __syncthreads();
+    double a[8], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { a[i] = row[bi + i]; b[i] = row[bj + i]; }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_fma(a[i], b[j], acc[i][j]);
+  }
+  double* out = C + static_cast<size_t>(h) * kH * kH;
+  const double inv = 1.0 / static_cast<double>(n_cal);
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) out[(bi + i) * kH + bj + j] = acc[i][j] * inv;
+}
+
+// Cyclic Jacobi on one symmetric 128 x 128 matrix per workgroup.  A round rotates 64
+// disjoint (p, q) planes at once (round-robin tournament order, 127 rounds per sweep):
+// angles from the current a_pp, a_qq, a_pq; then A <- J^T A J (columns, then rows) and
+// V <- V J.  Entries already at round-off level are set to zero instead of rotated.
+// Stops when the off-diagonal Frobenius norm is <= tol * ||A||_F or after max_sweeps.
+__global__ __launch_bounds__(1024) void jacobi128_kernel(const double* __restrict__ C,
+                                                         double* __restrict__ V_out,
+                                                         double* __restrict__ lam_out,
+                                                         int* __restrict__ sweeps_out, double tol,
+                                                         int max_sweeps) {
+  extern __shared__ double lds[];
+  double* A = lds;                         // [128][129]
+  double* cs = lds + kH * kLd;             // [64] cos, [64] sin
+  int* pq = reinterpret_cast<int*>(cs + 128);   // [64] p, [64] q
+  double* red = reinterpret_cast<double*>(pq + 128);   // [16] reduction scratch
+  const int h = blockIdx.x, tid = threadIdx.x;
+  double* V = V_out + static_cast<size_t>(h) * kH * kH;   // row-major [i][j], column j = vector j
+  const double* Ch = C + static_cast<size_t>(h) * kH * kH;
+
+  for (int i = tid; i < kH * kH; i += 1024) {
+    const int r = i >> 7, c = i & 127;
+    A[r * kLd + c] = 0.5 * (Ch[r * kH + c] + Ch[c * kH + r]);
+    V[i] = r == c ? 1.0 : 0.0;
+  }
+  __syncthreads();
+
+  auto block_sum = [&](double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    __syncthreads();
+    if ((tid & 63) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    double s = 0.0;
+    for (int w = 0; w < 16; ++w) s += red[w];
+    return s;
+  };
+  double part = 0.0;
+  for (int i = tid; i < kH * kH; i += 1024) { const double a = A[(i >> 7) * kLd + (i & 127)]; part += a * a; }
+  const double norm2 = block_sum(part);
+  const double tiny = 2.220446049250313e-16 * sqrt(norm2) / kH;
+  int sweep = 0;
+  if (norm2 > 0.0) {
+    for (; sweep < max_sweeps; ++sweep) {
+      part = 0.0;
+      for (int i = tid; i < kH * kH; i += 1024) {
+        const int r = i >> 7, c = i & 127;
+        if (r != c) { const double a = A[r * kLd + c]; part += a * a; }
+      }
+      const double off2 = block_sum(part);
+      if (off2 <= tol * tol * norm2) break;
+      for (int round = 0; round < kH - 1; ++round) {
+        // tournament: player 127 stays, players 0..126 rotate; slot k meets slot 127 - k
+        if (tid < 64) {
+          auto player = [&](int slot) { return slot == kH - 1 ? kH - 1 : (slot + round) % (kH - 1); };
+          const int a = player(tid), b = player(kH - 1 - tid);
+          const int p = a < b ? a : b, q = a < b ? b : a;
+          const double apq = A[p * kLd + q], app = A[p * kLd + p], aqq = A[q * kLd + q];
+          double c = 1.0, s = 0.0;
+          if (fabs(apq) > tiny) {
+            const double tau = (aqq - app) / (2.0 * apq);
+            const double t = tau == 0.0 ? 1.0 : copysign(1.0, tau) / (fabs(tau) + hypot(1.0, tau));
+            c = 1.0 / sqrt(1.0 + t * t);
+            s = t * c;
+          } else {
+            A[p * kLd + q] = 0.0;
+            A[q * kLd + p] = 0.0;
+          }
+          cs[tid] = c; cs[64 + tid] = s; pq[tid] = p; pq[64 + tid] = q;
+        }
+        __syncthreads();
+        // columns of A and of V: (x_p, x_q) <- (c x_p - s x_q, s x_p + c x_q) for every row
+        for (int w = tid; w < 64 * kH; w += 1024) {
+          const int k = w >> 7, i = w & 127;
+          const double c = cs[k], s = cs[64 + k];
+          const int p = pq[k], q = pq[64 + k];
+          const double ap = A[i * kLd + p], aq = A[i * kLd + q];
+          A[i * kLd + p] = c * ap - s * aq;
+          A[i * kLd + q] = s * ap + c * aq;
+          const double vp = V[i * kH + p], vq = V[i * kH + q];
+          V[i * kH + p] = c * vp - s * vq;
+          V[i * kH + q] = s * vp + c * vq;
+        }
+        __syncthreads();
+        // rows of A
+        for (int w = tid; w < 64 * kH; w += 1024) {
+          const int k = w >> 7, j = w & 127;
+          const double c = cs[k], s = cs[64 + k];
+          const int p = pq[k], q = pq[64 + k];
+          const double ap = A[p * kLd + j], aq = A[q * kLd + j];
+          A[p * kLd + j] = c * ap - s * aq;
+          A[q * kLd + j] = s * ap + c * aq;
+        }
+        __syncthreads();
+      }
+    }
+  }
+  if (tid < kH) lam_out[h * kH + tid] = A[tid * kLd + tid];
+  if (tid == 0) sweeps_out[h] = sweep;
+}
+
+static int pca_fail(hipError_t e, const char* what) {
+  set_error(std::string(what) + ": " + hipGetErrorString(e));
+  return ROSAQ_ERR_HIP;
+}
+
+// Device part + the host bookkeeping of Eq. 4's "columns sorted by eigenvalue": descending
+// order (ties keep the lower column first), negative round-off clamped to zero, each
+// eigenvector signed so that its entry of largest magnitude is positive.
+int pca_headwise_device(const void* X_dev, int n_cal, int D, int64_t ldx, float* Q_host,
+                        double* eig_host, void* stream) {
+  const int H = D / kH;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  double *dC = nullptr, *dV = nullptr, *dL = nullptr;
+  int* dS = nullptr;
+  const size_t mat = static_cast<size_t>(H) * kH * kH;
+  hipError_t e = hipMalloc(&dC, mat * 8);
+  if (e == hipSuccess) e = hipMalloc(&dV, mat * 8);
+  if (e == hipSuccess) e = hipMalloc(&dL, static_cast<size_t>(D) * 8);
+  if (e == hipSuccess) e = hipMalloc(&dS, static_cast<size_t>(H) * 4);
+  std::vector<double> V, lam(D);
+  std::vector<int> sweeps(H);
+  const size_t lds_bytes = (static_cast<size_t>(kH) * kLd + 128 + 16) * 8 + 128 * 4;
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi128_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(second_moment_kernel, dim3(H), dim3(256), 0, st,
+                       static_cast<const _Float16*>(X_dev), ldx, n_cal, dC);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(jacobi128_kernel, dim3(H), dim3(1024), lds_bytes, st, dC, dV, dL, dS, 1e-13, 60);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) {
+    try { V.resize(mat); } catch (const std::bad_alloc&) { e = hipErrorOutOfMemory; }
+  }
+  if (e == hipSuccess) e = hipMemcpyAsync(V.data(), dV, mat * 8, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipMemcpyAsync(lam.data(), dL, static_cast<size_t>(D) * 8, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipMemcpyAsync(sweeps.data(), dS, static_cast<size_t>(H) * 4, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (dC) (void)hipFree(dC);
+  if (dV) (void)hipFree(dV);
+  if (dL) (void)hipFree(dL);
+  if (dS) (void)hipFree(dS);
+  if (e != hipSuccess) return pca_fail(e, "rosaq_pca_headwise");
+  for (int h = 0; h < H; ++h)
+    if (sweeps[h] >= 60) {
+      set_error("Jacobi did not converge within 60 sweeps");
+      return ROSAQ_ERR_NONFINITE;
+    }
+  for (int h = 0; h < H; ++h) {
+    const double* Vh = &V[static_cast<size_t>(h) * kH * kH];
+    std::vector<int> order(kH);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int a, int b) { return lam[h * kH + a] > lam[h * kH + b]; });
+    float* Qh = Q_host + static_cast<size_t>(h) * kH * kH;
+    for (int j = 0; j < kH; ++j) {
+      const int src = order[j];
+      eig_host[h * kH + j] = std::max(lam[h * kH + src], 0.0);
+      int big = 0;
+      for (int i = 1; i < kH; ++i)
+        if (std::fabs(Vh[i * kH + src]) > std::fabs(Vh[big * kH + src])) big = i;
+      const double sign = Vh[big * kH + src] < 0.0 ? -1.0 : 1.0;
+      for (int i = 0; i < kH; ++i) Qh[i * kH + j] = static_cast<float>(sign * Vh[i * kH + src]);
+    }
+  }
+  return ROSAQ_OK;
+}
+
+}  // namespace rosaq

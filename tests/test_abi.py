@@ -179,3 +179,13 @@ def test_clone_of_host_only_handle():
     assert B.lib().rosaq_packed_clone(None, None, C.byref(out)) == -1
     assert B.lib().rosaq_packed_clone(c.handle, None, None) == -1
     c.free()
+
+
+def test_pca_headwise_argument_errors():
+    X = 0x10000
+    assert _code(lambda: B.rosaq_pca_headwise(0, 64, 256, 256)) == -1
+    assert _code(lambda: B.rosaq_pca_headwise(X, 0, 256, 256)) == -2
+    assert _code(lambda: B.rosaq_pca_headwise(X, 64, 200, 256)) == -2
+    assert _code(lambda: B.rosaq_pca_headwise(X, 64, 256, 128)) == -2
+    assert _code(lambda: B.rosaq_pca_headwise(X + 1, 64, 256, 256)) == -5
+    assert B.lib().rosaq_pca_headwise(X, 64, 256, 256, None, None, None) == -1

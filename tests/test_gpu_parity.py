@@ -237,3 +237,38 @@ def test_device_rotation_packs_the_same_bits_as_the_host_path():
     check_pack(p_dev, ref)
     check_pack(p_host, ref)
     p_dev.free(); p_host.free()
+
+
+@pytest.mark.parametrize("D,n_cal", [(256, 512), (1024, 700)])
+def test_pca_headwise_on_gpu_against_oracle(D, n_cal):
+    """Calibration on the GPU (second moment + Jacobi per head) against the oracle's PCA of the
+    same fp16 activations: eigenvalues to 1e-10, eigenvectors to fp32 resolution, orthogonality,
+    and the packed layer built from the GPU rotation equals the one built from the oracle's."""
+    print(f"case gpu pca D={D}", flush=True)
+    lay = synth.make_layer(55, 8, D, 64, n_cal)
+    X16 = lay["X_cal"].astype(np.float16)
+    Qo, lo = O.pca_headwise(X16, 128, "jacobi")
+    xd = torch.from_numpy(X16).cuda()
+    Qg, lg = B.rosaq_pca_headwise(xd.data_ptr(), n_cal, D, xd.stride(0))
+    assert np.all(np.diff(lg.reshape(-1, 128), axis=1) <= 0) and np.all(lg >= 0)
+    assert np.max(np.abs(lg - lo)) <= 1e-10 * lo.max()
+    for h in range(D // 128):
+        q = Qg[h].astype(np.float64)
+        assert np.max(np.abs(q.T @ q - np.eye(128))) <= 2e-6
+        big = np.argmax(np.abs(q), axis=0)
+        assert np.all(q[big, np.arange(128)] > 0)                       # sign convention
+        # well separated eigenvalues: same vectors up to sign (near-equal magnitudes may flip it)
+        gap = np.minimum(np.abs(np.diff(lo[h * 128:(h + 1) * 128], prepend=np.inf)),
+                         np.abs(np.diff(lo[h * 128:(h + 1) * 128], append=-np.inf)))
+        ok = gap > 1e-5 * lo[h * 128]
+        d = np.minimum(np.abs(q - Qo[h]).max(axis=0), np.abs(q + Qo[h]).max(axis=0))
+        assert np.max(d[ok]) <= 2e-6, np.max(d[ok])
+        # C_h = Q Lambda Q^T
+        Ch = O.second_moment(X16[:, h * 128:(h + 1) * 128])
+        assert np.linalg.norm(q @ np.diag(lg[h * 128:(h + 1) * 128]) @ q.T - Ch) <= 1e-5 * np.linalg.norm(Ch)
+    # the GPU rotation drives the rest of the pipeline like any other Q, lambda
+    ref = O.pack(lay["W"], Qg, lg, 128, 4, O.MODE_HEADWISE)
+    p = B.rosaq_pack_weights(lay["W"], Qg, lg, 128, 4, B.Q_HEADWISE)
+    check_pack(p, ref)
+    check_output(run_gpu(p, lay["x"]), lay["x"], Qg, ref)
+    p.free()
