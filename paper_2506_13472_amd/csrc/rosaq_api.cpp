@@ -15,6 +15,7 @@ static thread_local std::string g_error;
 void set_error(const std::string& s) { g_error = s; }
 
 static GemmTune g_tune;         // all zero = heuristics
+static GemmTune g_tune_rot;     // same, for the dense-rotation launch
 static int g_tune_stages = 3;  // bit 0: prologue kernels, bit 1: main GEMM (timing aid)
 
 static int fail(int code, const std::string& msg) {
@@ -208,10 +209,15 @@ static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_
     return launch_gather(x_dev, ldx, M, c.D, p->d_perm, ws + w.xf_a, hip_stream);
   // xhat = x fp16(Q): a dense fp16 contraction, run as an all-fp16 layer whose
   // "weight" is Q^T with rows already in storage order
-  int rc = launch_gather(x_dev, ldx, M, c.D, nullptr, ws + w.xf_a, hip_stream);
-  if (rc != ROSAQ_OK) return rc;
   GemmArgs a{};
   a.xf = ws + w.xf_a;
+  if (M <= 16) {
+    a.xrow = x_dev;        // skinny input: the rotation reads x in place, no fragment copy
+    a.ldx = ldx;
+  } else {
+    const int rc = launch_gather(x_dev, ldx, M, c.D, nullptr, ws + w.xf_a, hip_stream);
+    if (rc != ROSAQ_OK) return rc;
+  }
   a.nseg = 1;
   a.seg[0].wS = p->d_qf; a.seg[0].wq = nullptr; a.seg[0].sz = nullptr;
   a.seg[0].out = ws + w.xf_b; a.seg[0].ldo = 0; a.seg[0].N = c.D;
@@ -219,7 +225,7 @@ static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_
   a.M = M;
   a.ks_s = c.D / kKStep; a.G = 0; a.KS = c.D / kKStep; a.KS_out = c.D / kKStep;
   a.bits = 4; a.out_frag = 1;
-  return launch_gemm(a, g_tune, hip_stream);
+  return launch_gemm(a, g_tune_rot, hip_stream);
 }
 
 static int run_call(const rosaq_packed_t* const* ps, int count, const void* x_dev, int M,
@@ -424,6 +430,16 @@ int rosaq_tune(const char* key, int32_t value) {
     if (value != 0 && value != 4 && value != 8 && value != 16)
       return fail(ROSAQ_ERR_ARG, "wpb must be 0, 4, 8 or 16");
     g_tune.wpb = value; return ROSAQ_OK;
+  }
+  if (!std::strncmp(key, "rot_", 4)) {
+    const char* k = key + 4;
+    if (value < 0 || value > 4 || value == 3) {
+      if (!(std::strcmp(k, "depth") == 0 && value == 3)) return fail(ROSAQ_ERR_ARG, "bad rotation tuning value");
+    }
+    if (!std::strcmp(k, "mt")) { g_tune_rot.mt = value; return ROSAQ_OK; }
+    if (!std::strcmp(k, "nt")) { g_tune_rot.nt = value; return ROSAQ_OK; }
+    if (!std::strcmp(k, "depth")) { g_tune_rot.depth = value; return ROSAQ_OK; }
+    return fail(ROSAQ_ERR_ARG, "unknown tuning key");
   }
   if (!std::strcmp(key, "depth")) {
     if (value < 0 || value > 4) return fail(ROSAQ_ERR_ARG, "depth must be 0 to 4");

@@ -59,6 +59,8 @@ struct GemmSegArgs {
 };
 struct GemmArgs {
   const void* xf;        // xhat fragments  [mblocks][KS][4][64] x 16 B
+  const void* xrow;      // or (all-fp16 launches with ks_s % 4 == 0): row-major fp16 x, stride ldx
+  int64_t ldx;
   GemmSegArgs seg[kMaxBatch];
   int nseg;
   int M;                 // valid rows

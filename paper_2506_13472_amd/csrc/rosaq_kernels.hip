@@ -94,6 +94,8 @@ extern "C" int rosaq_debug_timeline(void* host, size_t bytes) {
 
 struct GemmDev {
   const uint4* xf;
+  const _Float16* xrow;   // all-fp16 launches only: read A fragments from row-major x instead of xf
+  int64_t ldx;
   GemmSeg seg[kMaxBatch];
   int nseg;
   int M, ks_s, G, KS, KS_out, out_frag, chunks, mgroups;
@@ -273,6 +275,69 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
   };
 
   const int ks_s = p.ks_s, G = p.G;
+  if constexpr (BITS == 16) {
+    // All-fp16 layer (the dense rotation, or K = D): no low-bit state, so the registers
+    // go to deep prefetch.  Units are runs of four k-steps; leftover k-steps go one by one.
+    struct QuadRegs {
+      uint4 a[4][MT];
+      uint4 b[4][NT];
+    };
+    auto load_quad = [&](int qd, QuadRegs& r) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          r.b[t][nt] = sg.wS[(static_cast<size_t>(tile0 + nt) * ks_s + 4 * qd + t) * 64 + lane];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          if (p.xrow != nullptr) {
+            // lane (row r, k-slice j) reads its 8 halves straight from x[m][32 (4 qd + t) + 8 j]
+            const int m = (mtile0 + mt) * 16 + (lane & 15);
+            r.a[t][mt] = make_uint4(0, 0, 0, 0);
+            if (m < p.M)
+              r.a[t][mt] = *reinterpret_cast<const uint4*>(p.xrow + static_cast<int64_t>(m) * p.ldx +
+                                                           (4 * qd + t) * kKStep + (lane >> 4) * 8);
+          } else {
+            r.a[t][mt] = row_ok ? xa[mt][static_cast<size_t>(4 * qd + t) * 256] : make_uint4(0, 0, 0, 0);
+          }
+        }
+      }
+    };
+    auto compute_quad = [&](const QuadRegs& r) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[nt][mt] = mfma16(as_h8(r.a[t][mt]), as_h8(r.b[t][nt]), acc[nt][mt]);
+    };
+    const int nquad = ks_s >> 2;
+    // fp16 tiles are a power-of-two number of KiB apart when D is: workgroups that all walk
+    // their tiles from k = 0 would camp on the same HBM channels.  Each workgroup starts
+    // its walk at its own offset (the sum over k does not care where it starts).
+    const int skew = nquad ? (blockIdx.x * 5) % nquad : 0;
+    auto at = [&](int i) { const int v = i + skew; return v >= nquad ? v - nquad : v; };
+    QuadRegs q[DEPTH];
+    int u = wave;
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+      if (u + d * WPB < nquad) load_quad(at(u + d * WPB), q[d]);
+    for (; u < nquad; u += DEPTH * WPB) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        if (u + d * WPB < nquad) {
+          compute_quad(q[d]);
+          if (u + (d + DEPTH) * WPB < nquad) load_quad(at(u + (d + DEPTH) * WPB), q[d]);
+        }
+      }
+    }
+    for (int st = 4 * nquad + wave; st < ks_s; st += WPB) {
+      StepRegs s0;
+      load_step(st, s0);
+      compute_step(s0);
+    }
+  } else {
   int u = wave;
   int g = (wave + WPB - ks_s % WPB) % WPB;
   StepRegs s0, s1;
@@ -302,6 +367,7 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
       }
     }
   }
+  }   // BITS != 16
   ROSAQ_STAMP(2)
 
 #ifdef ROSAQ_PROBE_NO_EPI
@@ -559,12 +625,21 @@ GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tu
   }
   s.depth = std::min(s.depth, max_depth);
   if (s.depth == 1 && s.mt * s.nt > 4 && s.mt * s.nt < 16) s.depth = 2;
+  if (bits == 16) {
+    // all-fp16 layers: a unit is four k-steps, 16 * (mt + nt) registers per unit in flight
+    s.wpb = 8;
+    const int per_unit = 16 * (s.mt + s.nt);
+    s.depth = tune.depth >= 1 && tune.depth <= 4 ? tune.depth : 3;
+    while (s.depth > 1 && s.depth * per_unit + 4 * s.mt * s.nt > 232) --s.depth;
+  }
   return s;
 }
 
 int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
   GemmDev d;
   d.xf = static_cast<const uint4*>(a.xf);
+  d.xrow = static_cast<const _Float16*>(a.xrow);
+  d.ldx = a.ldx;
   d.M = a.M; d.ks_s = a.ks_s; d.G = a.G; d.KS = a.KS; d.KS_out = a.KS_out;
   d.out_frag = a.out_frag;
   int ntiles_total = 0;
@@ -585,7 +660,7 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
   }
   d.chunks = chunks;
   d.mgroups = ((a.M + 15) / 16 + sh.mt - 1) / sh.mt;
-  const int bits = a.G == 0 ? 4 : a.bits;
+  const int bits = a.G == 0 ? 16 : a.bits;
   hipStream_t st = static_cast<hipStream_t>(stream);
 #define ROSAQ_CASE(B, MT_, NT_, W)                                              \
   if (bits == B && sh.mt == MT_ && sh.nt == NT_ && sh.wpb == W) {              \
@@ -602,6 +677,7 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
   ROSAQ_CASE(B, 1, 1, 16) ROSAQ_CASE(B, 1, 2, 16) ROSAQ_CASE(B, 2, 1, 16)
   ROSAQ_CASES(4)
   ROSAQ_CASES(3)
+  ROSAQ_CASES(16)
 #undef ROSAQ_CASES
 #undef ROSAQ_CASE
   set_error("no kernel for this bits / tile combination");
