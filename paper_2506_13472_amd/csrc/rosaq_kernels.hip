@@ -56,17 +56,24 @@ __device__ __forceinline__ half8 dequant4(uint32_t v, half2v c_lo, half2v c_hi) 
 
 // Eight 3-bit codes of k-step t: low two bits from the 2-bit plane dword `lo`
 // (fields 4*(t&1)+i), high bit from the 1-bit plane dword `hi` (fields 4*t+i).
+// Per fp16 pair: one shift + and-or for the low bits, one shift + and-or to drop the
+// high bit at mantissa bit 2; 0x6400 | q is 1024 + q.
 __device__ __forceinline__ half8 dequant3(uint32_t lo, uint32_t hi, int t, half2v c_lo) {
   const uint32_t kMagic = 0x64006400u;
   half2v h[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const uint32_t a = (lo >> (2 * (4 * (t & 1) + i))) & 0x00030003u;
-    const uint32_t b = ((hi >> (4 * t + i)) & 0x00010001u) << 2;
-    h[i] = as_h2(kMagic | a | b) + c_lo;
+    const int sl = 2 * (4 * (t & 1) + i);          // low field position
+    const int sh = 4 * t + i - 2;                  // high bit position minus its target bit 2
+    const uint32_t r = and_or(sl ? lo >> sl : lo, 0x00030003u, kMagic);
+    const uint32_t hs = sh > 0 ? hi >> sh : (sh < 0 ? hi << -sh : hi);
+    h[i] = as_h2(and_or(hs, 0x00040004u, r)) + c_lo;
   }
   return half8{h[0].x, h[0].y, h[1].x, h[1].y, h[2].x, h[2].y, h[3].x, h[3].y};
 }
+
+// 12-byte lane record of the INT3 image, read with one global_load_dwordx3
+struct __attribute__((aligned(4))) Code3 { uint32_t lo01, lo23, hi; };
 
 // One packed layer inside a launch.  A launch covers up to kMaxBatch layers that
 // share the rotated input (e.g. the q, k, v projections of one attention block).
@@ -222,9 +229,8 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
 #endif
         r.cw[nt][0] = c.x; r.cw[nt][1] = c.y; r.cw[nt][2] = c.z; r.cw[nt][3] = c.w;
       } else {
-        r.cw[nt][0] = sg.wq[fi * 3 + 0];
-        r.cw[nt][1] = sg.wq[fi * 3 + 1];
-        r.cw[nt][2] = sg.wq[fi * 3 + 2];
+        const Code3 c = reinterpret_cast<const Code3*>(sg.wq)[fi];
+        r.cw[nt][0] = c.lo01; r.cw[nt][1] = c.lo23; r.cw[nt][2] = c.hi;
         r.cw[nt][3] = 0;
       }
       r.sz[nt] = sg.sz[(static_cast<size_t>(tile0 + nt) * p.G + g) * 16 + (lane & 15)];
