@@ -412,7 +412,10 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
 }
 
 // xhat fragments from x by a column permutation (or identity): the prologue of
-// the rotation-less layer and of the dense rotation.
+// the rotation-less layer and of the dense rotation.  Storage order keeps channels
+// ascending inside the salient and inside the remaining part, so most 8-channel
+// fragments are a run of consecutive channels: those are cut out of two aligned
+// 16-byte loads; the others are gathered element by element.
 __global__ __launch_bounds__(256) void gather_kernel(const _Float16* __restrict__ x, int64_t ldx,
                                                      int M, int KS, const int32_t* __restrict__ perm,
                                                      uint4* __restrict__ xf, int total) {
@@ -428,11 +431,32 @@ __global__ __launch_bounds__(256) void gather_kernel(const _Float16* __restrict_
     if (perm == nullptr) {
       v = *reinterpret_cast<const uint4*>(row + p0);
     } else {
-      uint16_t h[8];
+      const int4 pa = *reinterpret_cast<const int4*>(perm + p0);
+      const int4 pb = *reinterpret_cast<const int4*>(perm + p0 + 4);
+      if (pb.w - pa.x == 7) {
+        const int base = pa.x & ~7, sh = pa.x & 7;
+        const uint4 lo = *reinterpret_cast<const uint4*>(row + base);
+        uint4 hi = make_uint4(0, 0, 0, 0);
+        if (sh) hi = *reinterpret_cast<const uint4*>(row + base + 8);   // sh > 0: the run reaches into it
+        const uint32_t w[9] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w, 0u};
+        uint32_t o[4] = {0, 0, 0, 0};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) h[e] = __builtin_bit_cast(uint16_t, row[perm[p0 + e]]);
-      v.x = h[0] | (uint32_t(h[1]) << 16); v.y = h[2] | (uint32_t(h[3]) << 16);
-      v.z = h[4] | (uint32_t(h[5]) << 16); v.w = h[6] | (uint32_t(h[7]) << 16);
+        for (int s2 = 0; s2 < 4; ++s2) {
+          if ((sh >> 1) == s2) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+              o[k] = (sh & 1) ? __builtin_amdgcn_alignbyte(w[k + s2 + 1], w[k + s2], 2) : w[k + s2];
+          }
+        }
+        v = make_uint4(o[0], o[1], o[2], o[3]);
+      } else {
+        const int c[8] = {pa.x, pa.y, pa.z, pa.w, pb.x, pb.y, pb.z, pb.w};
+        uint16_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = __builtin_bit_cast(uint16_t, row[c[e]]);
+        v.x = h[0] | (uint32_t(h[1]) << 16); v.y = h[2] | (uint32_t(h[3]) << 16);
+        v.z = h[4] | (uint32_t(h[5]) << 16); v.w = h[6] | (uint32_t(h[7]) << 16);
+      }
     }
   }
   xf[idx] = v;
