@@ -140,7 +140,7 @@ def shape_sweep(args):
         per_row = 2 * K + (D_ - K) * bits // 8 + 4 * (D_ - K) // GROUP
         rot_bytes = {"headwise": 2 * 128 * D_, "full": 2 * D_ * D_, "none": 0}[mode]
         calls = 32
-        for M_ in Ms:
+        for M_ in ([int(v) for v in args.sweep_m.split(",")] if args.sweep_m else Ms):
             x = torch.from_numpy(synth.make_activations(17, M_, D_)).to(dev)
             y = torch.empty((M_, N_), dtype=torch.float16, device=dev)
             ws = T.alloc_workspace(base, M_)
@@ -188,6 +188,7 @@ def main():
                     help="instead of the bench, time every MLP / attention shape of the task's configs "
                          "(one JSON line each)")
     ap.add_argument("--sweep-filter", default="", help="substring of the shape names to run")
+    ap.add_argument("--sweep-m", default="", help="comma-separated M values replacing each shape's own list")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of the bench, run 20 plain device copies of this size "
                          "(reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -195,6 +196,7 @@ def main():
     ap.add_argument("--nt", type=int, default=0, help="tuning aid: 16-channel tiles per workgroup")
     ap.add_argument("--wpb", type=int, default=0, help="tuning aid: waves per workgroup (8 or 16)")
     ap.add_argument("--depth", type=int, default=0, help="tuning aid: units in flight per wave (2-4)")
+    ap.add_argument("--lds", type=int, default=0, help="tuning aid: large-M LDS kernel 0 auto / 1 force / 2 never")
     ap.add_argument("--rot", default="", help="tuning aid: mt,nt,depth of the dense-rotation launch")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -219,6 +221,7 @@ def main():
     B.lib()
     for key in ("mt", "nt", "wpb", "depth"):
         B.rosaq_tune(key, getattr(args, key))
+    B.rosaq_tune("lds", args.lds)
     if args.rot:
         for key, v in zip(("rot_mt", "rot_nt", "rot_depth"), args.rot.split(",")):
             B.rosaq_tune(key, int(v))
