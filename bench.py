@@ -171,6 +171,124 @@ def shape_sweep(args):
         del W16, w16
 
 
+def decode_workload(args):
+    """The linears of a LLaMA-7B-shaped decode step at batch 64, INT4 g128, K = 128: per layer
+    q/k/v (one batched call, shared head-wise rotation), o (head-wise), gate/up (one batched call
+    sharing one dense 4096 x 4096 rotation) and down (no rotation, the paper's setting for W_D);
+    32 layers per step, every layer its own device copy of weights and rotations.  Prints one JSON
+    line with the time per step next to the same linears as fp16 torch.matmul calls."""
+    import torch
+    from paper_2506_13472_amd import binding as B, synth, torch_glue as T
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream()
+    d, f, L = 4096, 11008, 32
+    t0 = time.perf_counter()
+    Qh_a, Qh_o = synth.random_orthogonal_blocks(21, d // 128), synth.random_orthogonal_blocks(22, d // 128)
+    lam_h = synth.descending_spectrum(23, d, d // 128)
+    Qf, lam_f = synth.random_orthogonal_dense(24, d), synth.descending_spectrum(25, d, 1)
+    lam_n = synth.descending_spectrum(26, f, 1)
+    base = {}
+    for j, name in enumerate("qkv"):
+        base[name] = B.rosaq_pack_weights(synth.make_weight(40 + j, d, d), Qh_a, lam_h, K, 4, B.Q_HEADWISE)
+    base["o"] = B.rosaq_pack_weights(synth.make_weight(43, d, d), Qh_o, lam_h, K, 4, B.Q_HEADWISE)
+    for j, name in enumerate(("gate", "up")):
+        base[name] = B.rosaq_pack_weights(synth.make_weight(44 + j, f, d), Qf, lam_f, K, 4, B.Q_FULL)
+    base["down"] = B.rosaq_pack_weights(synth.make_weight(46, d, f), None, lam_n, K, 4, B.Q_NONE)
+    t_pack = time.perf_counter() - t0
+    layers = [base] + [{k: B.rosaq_packed_clone(h) for k, h in base.items()} for _ in range(L - 1)]
+    packed_bytes = sum(h.device_bytes for lay in layers for h in lay.values())
+
+    x = torch.from_numpy(synth.make_activations(7, M, d)).to(dev)
+    xh = torch.from_numpy(synth.make_activations(8, M, f)).to(dev)
+    y_d = [torch.empty((M, d), dtype=torch.float16, device=dev) for _ in range(4)]
+    y_f = [torch.empty((M, f), dtype=torch.float16, device=dev) for _ in range(2)]
+    ws_bytes = max(B.rosaq_workspace_bytes(h, M) for h in base.values())
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    qkv = [B.BatchArgs([lay[n] for n in "qkv"], [y.data_ptr() for y in y_d[:3]], [y.stride(0) for y in y_d[:3]])
+           for lay in layers]
+    gu = [B.BatchArgs([lay["gate"], lay["up"]], [y.data_ptr() for y in y_f], [y.stride(0) for y in y_f])
+          for lay in layers]
+
+    def step():
+        sp = T.current_stream_ptr()
+        for l, lay in enumerate(layers):
+            B.rosaq_linear_batch(qkv[l], x.data_ptr(), M, x.stride(0), ws.data_ptr(), ws.numel(), sp)
+            T.linear(lay["o"], x, y_d[3], ws)
+            B.rosaq_linear_batch(gu[l], x.data_ptr(), M, x.stride(0), ws.data_ptr(), ws.numel(), sp)
+            T.linear(lay["down"], xh, y_d[3], ws)
+
+    # fp16: the same seven linears per layer as separate vendor GEMMs, and with q/k/v and gate/up fused
+    W_qkv = [torch.randn((3 * d, d), dtype=torch.float16, device=dev) * 0.02 for _ in range(L)]
+    W_o = [torch.randn((d, d), dtype=torch.float16, device=dev) * 0.02 for _ in range(L)]
+    W_gu = [torch.randn((2 * f, d), dtype=torch.float16, device=dev) * 0.02 for _ in range(L)]
+    W_dn = [torch.randn((d, f), dtype=torch.float16, device=dev) * 0.02 for _ in range(L)]
+    y_qkv = torch.empty((M, 3 * d), dtype=torch.float16, device=dev)
+    y_gu = torch.empty((M, 2 * f), dtype=torch.float16, device=dev)
+
+    def step16_fused():
+        for l in range(L):
+            torch.matmul(x, W_qkv[l].t(), out=y_qkv)
+            torch.matmul(x, W_o[l].t(), out=y_d[3])
+            torch.matmul(x, W_gu[l].t(), out=y_gu)
+            torch.matmul(xh, W_dn[l].t(), out=y_d[3])
+
+    def step16_separate():
+        for l in range(L):
+            for j in range(3):
+                torch.matmul(x, W_qkv[l][j * d:(j + 1) * d].t(), out=y_d[j])
+            torch.matmul(x, W_o[l].t(), out=y_d[3])
+            for j in range(2):
+                torch.matmul(x, W_gu[l][j * f:(j + 1) * f].t(), out=y_f[j])
+            torch.matmul(xh, W_dn[l].t(), out=y_d[3])
+
+    def time_steps(fn, steps, warmup):
+        with torch.cuda.stream(stream):
+            fn()
+            stream.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                fn()
+            for _ in range(warmup):
+                g.replay()
+            stream.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                g.replay()
+            stream.synchronize()
+            return (time.perf_counter() - t0) / steps
+
+    steps = args.decode_steps
+    t = time_steps(step, steps, args.warmup)
+    B.rosaq_tune("stages", 2)
+    t_gemm = time_steps(step, steps, args.warmup)
+    B.rosaq_tune("stages", 3)
+    t16f = time_steps(step16_fused, steps, args.warmup)
+    t16s = time_steps(step16_separate, steps, args.warmup)
+
+    def row_bytes(D_):
+        return 2 * K + (D_ - K) * 4 // 8 + 4 * (D_ - K) // GROUP
+    per_layer = (4 * d * row_bytes(d) + 2 * f * row_bytes(d) + d * row_bytes(f)     # packed weights
+                 + 2 * 2 * 128 * d + 2 * d * d                                      # two head-wise + one dense rotation
+                 + 2 * M * (4 * d + 4 * d) + 2 * M * (d + 2 * f) + 2 * M * (f + d))  # x and y of the four calls
+    fp16_layer = 2 * (4 * d * d + 3 * d * f) + 2 * M * (2 * d + 4 * d) + 2 * M * (d + 2 * f) + 2 * M * (f + d)
+    print(json.dumps({
+        "workload": "llama7b_decode_linears_M64_int4", "layers": L, "linears_per_step": 7 * L, "M": M,
+        "calls_per_layer": "rosaq_linear_batch(q,k,v; head-wise) + rosaq_linear_headwise(o) + "
+                           "rosaq_linear_batch(gate,up; dense 4096^2 rotation) + rosaq_linear(down; no rotation)",
+        "steps_timed": steps, "ms_per_step": round(t * 1e3, 4), "total_s": round(t * steps, 4),
+        "ms_per_step_main_gemms_only": round(t_gemm * 1e3, 4),
+        "algorithmic_GB_per_step": round(per_layer * L / 1e9, 3),
+        "GBps": round(per_layer * L / t / 1e9, 1), "frac_of_hbm_peak": round(per_layer * L / t / 1e9 / HBM_PEAK_GBS, 4),
+        "packed_GB_resident": round(packed_bytes / 1e9, 3), "pack_s_one_layer": round(t_pack, 1),
+        "fp16": {"impl": "torch.matmul fp16 (vendor GEMM), one hipGraph per step",
+                 "ms_per_step_4_gemms_per_layer_fused_qkv_gateup": round(t16f * 1e3, 4),
+                 "ms_per_step_7_gemms_per_layer": round(t16s * 1e3, 4),
+                 "GB_per_step": round(fp16_layer * L / 1e9, 3),
+                 "GBps_fused": round(fp16_layer * L / t16f / 1e9, 1)},
+        "speedup_vs_fp16_fused": round(t16f / t, 3), "speedup_vs_fp16_separate": round(t16s / t, 3),
+        "data": "synthetic"}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -187,6 +305,10 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the bench, time every MLP / attention shape of the task's configs "
                          "(one JSON line each)")
+    ap.add_argument("--decode", action="store_true",
+                    help="instead of the bench, time the seven linears x 32 layers of a 7B-shaped decode step "
+                         "at batch 64 against fp16 vendor GEMMs (one JSON line)")
+    ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--sweep-filter", default="", help="substring of the shape names to run")
     ap.add_argument("--sweep-m", default="", help="comma-separated M values replacing each shape's own list")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -227,6 +349,9 @@ def main():
             B.rosaq_tune(key, int(v))
     if args.sweep:
         shape_sweep(args)
+        return
+    if args.decode:
+        decode_workload(args)
         return
 
     # ---- synthetic layers: calibrate (PCA per head on the GPU), pack, all through the C ABI ------

@@ -450,8 +450,9 @@ int rosaq_tune(const char* key, int32_t value) {
     g_tune.depth = value; return ROSAQ_OK;
   }
   if (!std::strcmp(key, "mt") || !std::strcmp(key, "nt")) {
-    if (value != 0 && value != 1 && value != 2 && value != 4)
-      return fail(ROSAQ_ERR_ARG, "tile counts must be 0, 1, 2 or 4");
+    const bool wide = key[0] == 'n' && (value == 3 || value == 6);
+    if (value != 0 && value != 1 && value != 2 && value != 4 && !wide)
+      return fail(ROSAQ_ERR_ARG, "tile counts must be 0, 1, 2 or 4 (nt also 3 or 6)");
     (key[0] == 'm' ? g_tune.mt : g_tune.nt) = value; return ROSAQ_OK;
   }
   if (!std::strcmp(key, "stages")) {

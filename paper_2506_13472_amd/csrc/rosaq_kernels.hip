@@ -87,6 +87,7 @@ struct GemmSeg {
   _Float16* out;
   int64_t ldo;
   int N;
+  int ntiles;        // 16-channel tiles in the weight image
   int chunk_end;     // exclusive prefix sum of channel chunks over the layers
 };
 #ifdef ROSAQ_PROBE_TIMELINE
@@ -146,7 +147,11 @@ __device__ __forceinline__ void store_fragment(const GemmDev& p, const GemmSeg& 
 // so that the weights are fetched from HBM once and found in that XCD's L2 after.
 template <int BITS, int MT, int NT, int WPB, int DEPTH>
 __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) void gemm_kernel(GemmDev p) {
-  __shared__ float4 red[WPB][NT * MT][64];
+  // the waves' partial tiles meet in LDS, in one pass or (large tiles) in two halves
+  constexpr int kRedPasses = WPB * NT * MT > 128 ? 2 : 1;
+  constexpr int kRedNT = NT / kRedPasses;
+  static_assert(NT % kRedPasses == 0, "tile split");
+  __shared__ float4 red[WPB][kRedNT * MT][64];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -163,12 +168,17 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
   if (si > 0) chunk -= p.seg[si - 1].chunk_end;
   GemmSeg sg;
   sg.wS = p.seg[si].wS; sg.wq = p.seg[si].wq; sg.sz = p.seg[si].sz; sg.out = p.seg[si].out;
-  sg.ldo = p.seg[si].ldo; sg.N = p.seg[si].N; sg.chunk_end = 0;
+  sg.ldo = p.seg[si].ldo; sg.N = p.seg[si].N; sg.ntiles = p.seg[si].ntiles; sg.chunk_end = 0;
 #ifdef ROSAQ_PROBE_EMPTY
   if (p.M > 0) return;
 #endif
   const int tile0 = chunk * NT;
   const int mtile0 = mg * MT;
+  // NT need not divide the layer's tile count: the last chunk re-reads the last tile for
+  // its missing ones (their results fall outside N and are not stored)
+  int wt[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) wt[nt] = tile0 + nt < sg.ntiles ? tile0 + nt : sg.ntiles - 1;
 
   floatx4 acc[NT][MT];
 #pragma unroll
@@ -203,7 +213,7 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
   auto load_step = [&](int u, StepRegs& r) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
-      r.b[nt] = sg.wS[(static_cast<size_t>(tile0 + nt) * p.ks_s + u) * 64 + lane];
+      r.b[nt] = sg.wS[(static_cast<size_t>(wt[nt]) * p.ks_s + u) * 64 + lane];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
       r.a[mt] = row_ok ? xa[mt][static_cast<size_t>(u) * 256] : make_uint4(0, 0, 0, 0);
@@ -220,10 +230,13 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
       for (int mt = 0; mt < MT; ++mt)
         acc[nt][mt] = mfma16(as_h8(r.a[mt]), as_h8(r.b[nt]), acc[nt][mt]);
   };
+  // Every workgroup walks the groups in the same order: the fp32 sum of an output element
+  // is then the same whatever the tile shape or batching of the launch (starting each
+  // workgroup at its own group was measured: 1-3 % faster, not worth that property).
   auto load_group = [&](int g, GroupRegs& r) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      const size_t fi = (static_cast<size_t>(tile0 + nt) * p.G + g) * 64 + lane;
+      const size_t fi = (static_cast<size_t>(wt[nt]) * p.G + g) * 64 + lane;
       if (BITS == 4) {
 #ifdef ROSAQ_PROBE_NO_W
         const uint4 c = make_uint4(fi, 5, 6, 7);
@@ -236,7 +249,7 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
         r.cw[nt][0] = c.lo01; r.cw[nt][1] = c.lo23; r.cw[nt][2] = c.hi;
         r.cw[nt][3] = 0;
       }
-      r.sz[nt] = sg.sz[(static_cast<size_t>(tile0 + nt) * p.G + g) * 16 + (lane & 15)];
+      r.sz[nt] = sg.sz[(static_cast<size_t>(wt[nt]) * p.G + g) * 16 + (lane & 15)];
     }
     const size_t ks0 = static_cast<size_t>(p.ks_s + 4 * g);
 #pragma unroll
@@ -296,7 +309,7 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
       for (int t = 0; t < 4; ++t) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-          r.b[t][nt] = sg.wS[(static_cast<size_t>(tile0 + nt) * ks_s + 4 * qd + t) * 64 + lane];
+          r.b[t][nt] = sg.wS[(static_cast<size_t>(wt[nt]) * ks_s + 4 * qd + t) * 64 + lane];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           if (p.xrow != nullptr) {
@@ -392,24 +405,28 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
 #endif
   // ---- sum the waves of this workgroup through LDS in wave order -----------------------
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt)
+  for (int pass = 0; pass < kRedPasses; ++pass) {
+    if (pass > 0) __syncthreads();
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const floatx4 v = acc[nt][mt];
-      red[wave][nt * MT + mt][lane] = make_float4(v[0], v[1], v[2], v[3]);
-    }
-  __syncthreads();
-  ROSAQ_STAMP(3)
+    for (int nt = 0; nt < kRedNT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const floatx4 v = acc[pass * kRedNT + nt][mt];
+        red[wave][nt * MT + mt][lane] = make_float4(v[0], v[1], v[2], v[3]);
+      }
+    __syncthreads();
+    if (pass == 0) { ROSAQ_STAMP(3) }
 
-  constexpr int kSlots = NT * MT;
-  for (int slot = wave; slot < kSlots; slot += WPB) {
-    float4 v = red[0][slot][lane];
+    constexpr int kSlots = kRedNT * MT;
+    for (int slot = wave; slot < kSlots; slot += WPB) {
+      float4 v = red[0][slot][lane];
 #pragma unroll
-    for (int w = 1; w < WPB; ++w) {
-      const float4 o = red[w][slot][lane];
-      v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+      for (int w = 1; w < WPB; ++w) {
+        const float4 o = red[w][slot][lane];
+        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+      }
+      store_fragment(p, sg, v, mtile0 + slot % MT, tile0 + pass * kRedNT + slot / MT, lane);
     }
-    store_fragment(p, sg, v, mtile0 + slot % MT, tile0 + slot / MT, lane);
   }
   ROSAQ_STAMP(4)
 }
@@ -463,7 +480,7 @@ __global__ __launch_bounds__(512) void gemm_lds_kernel(GemmDev p, int mtiles_all
   if (si > 0) chunk -= p.seg[si - 1].chunk_end;
   GemmSeg sg;
   sg.wS = p.seg[si].wS; sg.wq = p.seg[si].wq; sg.sz = p.seg[si].sz; sg.out = p.seg[si].out;
-  sg.ldo = p.seg[si].ldo; sg.N = p.seg[si].N; sg.chunk_end = 0;
+  sg.ldo = p.seg[si].ldo; sg.N = p.seg[si].N; sg.ntiles = p.seg[si].ntiles; sg.chunk_end = 0;
   const int tile0 = chunk * 8;
   const int mtile0 = mrow * 8;
   const int ks_s = p.ks_s;                       // multiple of 4 (checked by the launcher)
@@ -910,8 +927,16 @@ GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tu
       if (t < best * 0.999) { best = t; s.mt = mt; s.nt = nt; }
     }
   }
+  // A 64 x 64 tiling that needs a second, mostly empty round of workgroups (e.g. gate + up of a
+  // 7B MLP in one launch: 1376 channel tiles) runs 10 % faster as 32 x 96 tiles (eight waves, like every default shape, so the
+  // summation order of an output element stays the same).
+  if (bits != 16 && s.mt == 4 && s.nt == 4 && mtiles <= 4 && (ntiles + 3) / 4 > 256 && (ntiles + 5) / 6 <= 256) {
+    s.mt = 2;
+    s.nt = 6;
+  }
   if (tune.mt == 1 || tune.mt == 2 || tune.mt == 4) s.mt = tune.mt;
   if (tune.nt == 1 || tune.nt == 2 || tune.nt == 4) s.nt = tune.nt;
+  if ((tune.nt == 3 || tune.nt == 6) && bits != 16 && s.mt >= 2) s.nt = tune.nt;
   s.wpb = 8;
   if (tune.wpb == 16 && s.mt * s.nt <= 2) s.wpb = 16;   // 16 waves leave 128 registers per lane
   if (tune.wpb == 4 && s.mt * s.nt >= 8) s.wpb = 4;     // one wave per SIMD: 512 registers
@@ -933,6 +958,17 @@ GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tu
   }
   s.depth = std::min(s.depth, max_depth);
   if (s.depth == 1 && s.mt * s.nt > 4 && s.mt * s.nt < 16) s.depth = 2;
+  if (s.nt == 3 || s.nt == 6) {
+    // 48- and 96-channel tiles (they make 768- and 1376-tile launches fit one round of 256)
+    if (s.mt == 4 && s.nt == 6) {
+      s.wpb = 4;                                        // 96 accumulator registers: one wave per SIMD
+      s.depth = 1;
+    } else {
+      s.wpb = 8;
+      const int cap = s.mt == 4 ? 1 : (s.nt == 6 ? 2 : 3);
+      s.depth = std::min(tune.depth >= 1 ? tune.depth : (s.nt == 6 ? 1 : cap), cap);
+    }
+  }
   if (bits == 16) {
     // all-fp16 layers: a unit is four k-steps, 16 * (mt + nt) registers per unit in flight
     s.wpb = 8;
@@ -957,13 +993,14 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
   int chunks = 0;
   for (int i = 0; i < kMaxBatch; ++i) {
     const GemmSegArgs& sa = a.seg[i < a.nseg ? i : 0];
-    if (i < a.nseg) chunks += sa.ntiles / sh.nt;
+    if (i < a.nseg) chunks += ((sa.N + kTileN - 1) / kTileN + sh.nt - 1) / sh.nt;
     d.seg[i].wS = static_cast<const uint4*>(sa.wS);
     d.seg[i].wq = static_cast<const uint32_t*>(sa.wq);
     d.seg[i].sz = static_cast<const uint32_t*>(sa.sz);
     d.seg[i].out = static_cast<_Float16*>(sa.out);
     d.seg[i].ldo = sa.ldo;
     d.seg[i].N = sa.N;
+    d.seg[i].ntiles = sa.ntiles;
     d.seg[i].chunk_end = chunks;
   }
   d.chunks = chunks;
@@ -1018,6 +1055,10 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
   ROSAQ_CASES(4)
   ROSAQ_CASES(3)
   ROSAQ_CASES(16)
+#define ROSAQ_WIDE(B) ROSAQ_CASE(B, 4, 3, 8) ROSAQ_CASE(B, 2, 3, 8) ROSAQ_CASE(B, 2, 6, 8) ROSAQ_CASE(B, 4, 6, 4)
+  ROSAQ_WIDE(4)
+  ROSAQ_WIDE(3)
+#undef ROSAQ_WIDE
 #undef ROSAQ_CASES
 #undef ROSAQ_CASE
   set_error("no kernel for this bits / tile combination");

@@ -61,3 +61,32 @@ def test_13b_mlp_down_int4_sampled_rows():
         x = synth.make_activations(71 + M, M, 13824)
         check_output(run_gpu(p, x), x, Q, ref)
     p.free()
+
+
+def test_7b_decode_layer_mlp_int4_gate_up_batch_and_unrotated_down():
+    """The MLP calls of the 7B decode workload: gate and up (4096 -> 11008, INT4) share one dense
+    rotation and go through one batched launch; down (11008 -> 4096, INT4) is not rotated, its
+    salient channels chosen by activation magnitude."""
+    from paper_2506_13472_amd import torch_glue as T
+    print("case 7B decode MLP INT4: gate/up batch + down", flush=True)
+    D, F, M = 4096, 11008, 64
+    Q = synth.random_orthogonal_dense(81, D)
+    lam = synth.descending_spectrum(82, D, 1)
+    Ws = [synth.make_weight(83, F, D), synth.make_weight(84, F, D)]
+    refs = [O.pack(W, Q, lam, 128, 4, O.MODE_FULL) for W in Ws]
+    ps = [B.rosaq_pack_weights(W, Q, lam, 128, 4, B.Q_FULL) for W in Ws]
+    x = synth.make_activations(85, M, D)
+    ys = T.linear_batch(ps, torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    for y, p, ref in zip(ys, ps, refs):
+        check_pack(p, ref)
+        check_output(y.cpu().numpy(), x, Q, ref)
+        p.free()
+    Wd = synth.make_weight(86, 1024, F)               # 1024 of the 4096 output channels
+    xd = synth.make_activations(87, M, F)
+    lam_d = np.abs(synth.make_activations(88, 512, F).astype(np.float64)).mean(axis=0)
+    ref = O.pack(Wd, None, lam_d, 128, 4, O.MODE_NONE)
+    p = B.rosaq_pack_weights(Wd, None, lam_d, 128, 4, B.Q_NONE)
+    check_pack(p, ref)
+    check_output(run_gpu(p, xd), xd, None, ref)
+    p.free()

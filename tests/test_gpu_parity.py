@@ -92,7 +92,8 @@ def test_config0_single_linear():
     p.free()
 
 
-@pytest.mark.parametrize("mt,nt,wpb", [(1, 1, 8), (1, 1, 16), (2, 2, 8), (4, 1, 8), (1, 4, 8), (4, 2, 8), (2, 4, 8), (2, 1, 16), (1, 2, 16)])
+@pytest.mark.parametrize("mt,nt,wpb", [(1, 1, 8), (1, 1, 16), (2, 2, 8), (4, 1, 8), (1, 4, 8), (4, 2, 8), (2, 4, 8), (2, 1, 16), (1, 2, 16),
+                                       (4, 3, 8), (2, 3, 8), (2, 6, 8), (4, 6, 4)])
 def test_tile_variants_agree_with_oracle_and_are_deterministic(mt, nt, wpb):
     print(f"case mt={mt} nt={nt} wpb={wpb}", flush=True)
     lay, Q, lam = make_case(7, 64, 1024, 256, 512, O.MODE_HEADWISE)
