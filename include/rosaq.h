@@ -187,7 +187,8 @@ int rosaq_stream_probe(const void* src_dev, size_t src_bytes, const void* shared
                        int32_t threads, void* sink_dev, size_t sink_bytes, void* hip_stream);
 
 /* Tuning aid for benchmarks; affects later rosaq_linear* calls in this process.
- *   "mt", "nt"  16-row / 16-channel MFMA tiles per workgroup (0 = heuristic, 1, 2, 4)
+ *   "mt", "nt"  16-row / 16-channel MFMA tiles per workgroup (0 = heuristic, 1, 2, 4; nt also 3 and 6
+ *             for low-bit layers with mt >= 2)
  *   "rot_mt", "rot_nt", "rot_depth"  the same three knobs for the dense-rotation launch
  *   "lds"     the LDS-tiled 128 x 128 kernel for prefill-sized calls: 0 = automatic (M >= 2048 and
  *             at least 256 tiles), 1 = whenever the layer's K is a multiple of 128, 2 = never.  Its
