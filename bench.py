@@ -188,11 +188,15 @@ def decode_workload(args):
     Qf, lam_f = synth.random_orthogonal_dense(24, d), synth.descending_spectrum(25, d, 1)
     lam_n = synth.descending_spectrum(26, f, 1)
     base = {}
+    ab = bool(args.absorbed)      # rotations folded into the producing layers offline (Sec. 3.1, App. G)
     for j, name in enumerate("qkv"):
-        base[name] = B.rosaq_pack_weights(synth.make_weight(40 + j, d, d), Qh_a, lam_h, K, 4, B.Q_HEADWISE)
-    base["o"] = B.rosaq_pack_weights(synth.make_weight(43, d, d), Qh_o, lam_h, K, 4, B.Q_HEADWISE)
+        base[name] = B.rosaq_pack_weights(synth.make_weight(40 + j, d, d), Qh_a, lam_h, K, 4, B.Q_HEADWISE,
+                                          rotation_absorbed=ab)
+    base["o"] = B.rosaq_pack_weights(synth.make_weight(43, d, d), Qh_o, lam_h, K, 4, B.Q_HEADWISE,
+                                     rotation_absorbed=ab)
     for j, name in enumerate(("gate", "up")):
-        base[name] = B.rosaq_pack_weights(synth.make_weight(44 + j, f, d), Qf, lam_f, K, 4, B.Q_FULL)
+        base[name] = B.rosaq_pack_weights(synth.make_weight(44 + j, f, d), Qf, lam_f, K, 4, B.Q_FULL,
+                                          rotation_absorbed=ab)
     base["down"] = B.rosaq_pack_weights(synth.make_weight(46, d, f), None, lam_n, K, 4, B.Q_NONE)
     t_pack = time.perf_counter() - t0
     layers = [base] + [{k: B.rosaq_packed_clone(h) for k, h in base.items()} for _ in range(L - 1)]
@@ -268,13 +272,16 @@ def decode_workload(args):
     def row_bytes(D_):
         return 2 * K + (D_ - K) * 4 // 8 + 4 * (D_ - K) // GROUP
     per_layer = (4 * d * row_bytes(d) + 2 * f * row_bytes(d) + d * row_bytes(f)     # packed weights
-                 + 2 * 2 * 128 * d + 2 * d * d                                      # two head-wise + one dense rotation
+                 + (0 if ab else 2 * 2 * 128 * d + 2 * d * d)                       # two head-wise + one dense rotation
                  + 2 * M * (4 * d + 4 * d) + 2 * M * (d + 2 * f) + 2 * M * (f + d))  # x and y of the four calls
     fp16_layer = 2 * (4 * d * d + 3 * d * f) + 2 * M * (2 * d + 4 * d) + 2 * M * (d + 2 * f) + 2 * M * (f + d)
     print(json.dumps({
-        "workload": "llama7b_decode_linears_M64_int4", "layers": L, "linears_per_step": 7 * L, "M": M,
-        "calls_per_layer": "rosaq_linear_batch(q,k,v; head-wise) + rosaq_linear_headwise(o) + "
-                           "rosaq_linear_batch(gate,up; dense 4096^2 rotation) + rosaq_linear(down; no rotation)",
+        "workload": "llama7b_decode_linears_M64_int4" + ("_rotations_absorbed" if ab else ""),
+        "layers": L, "linears_per_step": 7 * L, "M": M,
+        "calls_per_layer": ("rosaq_linear_batch(q,k,v) + rosaq_linear(o) + rosaq_linear_batch(gate,up) + "
+                            "rosaq_linear(down): inputs arrive rotated, run time only permutes them") if ab else
+                           ("rosaq_linear_batch(q,k,v; head-wise) + rosaq_linear_headwise(o) + "
+                            "rosaq_linear_batch(gate,up; dense 4096^2 rotation) + rosaq_linear(down; no rotation)"),
         "steps_timed": steps, "ms_per_step": round(t * 1e3, 4), "total_s": round(t * steps, 4),
         "ms_per_step_main_gemms_only": round(t_gemm * 1e3, 4),
         "algorithmic_GB_per_step": round(per_layer * L / 1e9, 3),
@@ -309,6 +316,9 @@ def main():
                     help="instead of the bench, time the seven linears x 32 layers of a 7B-shaped decode step "
                          "at batch 64 against fp16 vendor GEMMs (one JSON line)")
     ap.add_argument("--decode-steps", type=int, default=256)
+    ap.add_argument("--absorbed", action="store_true",
+                    help="with --decode: pack every layer with rotation_absorbed (the paper's deployment: "
+                         "rotations folded into the producing layers offline, no rotation at run time)")
     ap.add_argument("--sweep-filter", default="", help="substring of the shape names to run")
     ap.add_argument("--sweep-m", default="", help="comma-separated M values replacing each shape's own list")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
