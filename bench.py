@@ -328,7 +328,6 @@ def main():
     ap.add_argument("--nt", type=int, default=0, help="tuning aid: 16-channel tiles per workgroup")
     ap.add_argument("--wpb", type=int, default=0, help="tuning aid: waves per workgroup (8 or 16)")
     ap.add_argument("--depth", type=int, default=0, help="tuning aid: units in flight per wave (2-4)")
-    ap.add_argument("--lds", type=int, default=0, help="tuning aid: large-M LDS kernel 0 auto / 1 force / 2 never")
     ap.add_argument("--rot", default="", help="tuning aid: mt,nt,depth of the dense-rotation launch")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -353,7 +352,6 @@ def main():
     B.lib()
     for key in ("mt", "nt", "wpb", "depth"):
         B.rosaq_tune(key, getattr(args, key))
-    B.rosaq_tune("lds", args.lds)
     if args.rot:
         for key, v in zip(("rot_mt", "rot_nt", "rot_depth"), args.rot.split(",")):
             B.rosaq_tune(key, int(v))

@@ -190,10 +190,6 @@ int rosaq_stream_probe(const void* src_dev, size_t src_bytes, const void* shared
  *   "mt", "nt"  16-row / 16-channel MFMA tiles per workgroup (0 = heuristic, 1, 2, 4; nt also 3 and 6
  *             for low-bit layers with mt >= 2)
  *   "rot_mt", "rot_nt", "rot_depth"  the same three knobs for the dense-rotation launch
- *   "lds"     the LDS-tiled 128 x 128 kernel for prefill-sized calls: 0 = automatic (M >= 2048 and
- *             at least 256 tiles), 1 = whenever the layer's K is a multiple of 128, 2 = never.  Its
- *             outputs can differ from the default kernel's in the last fp16 bit (weights are
- *             rounded to fp16 after scaling there).
  *   "wpb"     waves per workgroup splitting the contraction (0 = default, 8, 16)
  *   "stages"  3 = whole call (default), 1 = prologue kernels only, 2 = main GEMM only
  *             (2 reuses the rotated activations a previous call left in the workspace) */

@@ -441,10 +441,6 @@ int rosaq_tune(const char* key, int32_t value) {
     if (!std::strcmp(k, "depth")) { g_tune_rot.depth = value; return ROSAQ_OK; }
     return fail(ROSAQ_ERR_ARG, "unknown tuning key");
   }
-  if (!std::strcmp(key, "lds")) {
-    if (value < 0 || value > 2) return fail(ROSAQ_ERR_ARG, "lds must be 0 (auto), 1 (force) or 2 (never)");
-    g_tune.lds = value; return ROSAQ_OK;
-  }
   if (!std::strcmp(key, "depth")) {
     if (value < 0 || value > 4) return fail(ROSAQ_ERR_ARG, "depth must be 0 to 4");
     g_tune.depth = value; return ROSAQ_OK;

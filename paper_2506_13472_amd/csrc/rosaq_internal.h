@@ -71,7 +71,7 @@ struct GemmArgs {
   int bits;              // 3 or 4 (ignored when G == 0)
   int out_frag;          // 0: y row-major, 1: xhat fragment order
 };
-struct GemmTune { int mt = 0, nt = 0, wpb = 0, depth = 0, lds = 0; };   // 0 = heuristic; lds: 1 force, 2 never
+struct GemmTune { int mt = 0, nt = 0, wpb = 0, depth = 0; };   // 0 = heuristic
 struct GemmShape { int mt, nt, wpb, depth; };
 GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tune);
 int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream);

@@ -13,7 +13,6 @@
 // fetches a fragment with one global_load_dwordx4 per lane, 1 KiB contiguous.
 #include <hip/hip_runtime.h>
 
-#include <type_traits>
 
 #include <algorithm>
 #include <cmath>
@@ -23,7 +22,6 @@
 namespace rosaq {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
@@ -112,6 +110,31 @@ struct GemmDev {
   int M, ks_s, G, KS, KS_out, out_frag, chunks, mgroups;
 };
 
+// Block -> (channel chunk, row group).  blockIdx % 8 is the XCD a workgroup lands on; each
+// XCD owns the chunks congruent to its number.  Inside an XCD consecutive workgroups, which
+// run at the same time, form blocks of 8 chunks x up to 4 row groups: they share the weights
+// of 8 chunks and the activations of 4 row groups through that XCD's L2, instead of one
+// chunk and every row group (which at large M streams the whole activation matrix through
+// every L2 once per chunk).  For up to 4 row groups this is the plain order: chunk-major.
+constexpr int kMapCols = 8, kMapRows = 4;
+__device__ __forceinline__ bool map_block(int b, int chunks, int mgroups, int& chunk, int& mg) {
+  const int xcd = b & 7, local = b >> 3;
+  const int tr = mgroups < kMapRows ? mgroups : kMapRows;
+  const int cx = (chunks + 7) >> 3;                       // chunk slots of one XCD
+  const int nbc = (cx + kMapCols - 1) / kMapCols;
+  const int block = local / (kMapCols * tr), inner = local - block * (kMapCols * tr);
+  const int ci = (block % nbc) * kMapCols + inner / tr;
+  mg = (block / nbc) * tr + inner % tr;
+  chunk = xcd + 8 * ci;
+  return ci < cx && chunk < chunks && mg < mgroups;
+}
+static int map_grid(int chunks, int mgroups) {
+  const int tr = mgroups < kMapRows ? mgroups : kMapRows;
+  const int cx = (chunks + 7) / 8;
+  const int nbc = (cx + kMapCols - 1) / kMapCols;
+  return 8 * nbc * ((mgroups + tr - 1) / tr) * kMapCols * tr;
+}
+
 // Store one accumulator fragment of row tile `mtile` (16 rows) and channel tile
 // `tile`: lane holds rows 4*(lane/16)+i, column lane%16.
 __device__ __forceinline__ void store_fragment(const GemmDev& p, const GemmSeg& sg, float4 v,
@@ -155,10 +178,8 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  int chunk = xcd + 8 * (local / p.mgroups);
-  const int mg = local % p.mgroups;
-  if (chunk >= p.chunks) return;
+  int chunk, mg;
+  if (!map_block(blockIdx.x, p.chunks, p.mgroups, chunk, mg)) return;
   ROSAQ_STAMP(0)
   // which layer of the batch this chunk belongs to (uniform over the workgroup)
   int si = 0;
@@ -431,281 +452,6 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
   ROSAQ_STAMP(4)
 }
 
-// Compile-time loop: f(integral_constant<int, I>) for I in [I0, N).
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
-  }
-}
-
-template <int I, class T>
-__device__ __forceinline__ T& pick4(T& a, T& b, T& c, T& d) {
-  static_assert(I >= 0 && I < 4, "slot index");
-  if constexpr (I == 0) return a;
-  else if constexpr (I == 1) return b;
-  else if constexpr (I == 2) return c;
-  else return d;
-}
-
-// Large-M variant (M >= 128): a workgroup of eight waves owns a 128 x 128 output tile over
-// the whole contraction, which it walks in stages of two k-steps (64 channels).  Waves 0-3
-// multiply: wave (wm, wn) owns the 64 x 64 quarter and reads both operands from LDS.  Waves
-// 4-7 feed them: they hold the next units (four k-steps: one quantisation group, or four
-// fp16 k-steps of a dense layer) in registers while those are on their way from memory (a ring
-// of PD units), dequantise every weight once per 128 rows and write activation and weight
-// fragments two stages ahead into a ring of three LDS buffers, so the multiplying waves can
-// request the first fragments of stage s + 1 while they finish stage s.  Low-bit weights are
-// written to LDS as fp16(s * (q - z)): one extra rounding of relative size 2^-11 per weight
-// against the small-M kernel, which applies s in fp32 to a per-group partial sum; in exchange
-// the multiplying waves do nothing but MFMAs.  One barrier per stage, executed by all eight
-// waves: both roles count 1 + stages barriers.
-constexpr int kLdsBufU4 = 2 * 16 * 64;     // per buffer: A [2 t][8 mt][64] and B [2 t][8 nt][64] 16-byte
-constexpr size_t kLdsKernelBytes = 3 * static_cast<size_t>(kLdsBufU4) * 16;
-
-template <int BITS>
-__global__ __launch_bounds__(512) void gemm_lds_kernel(GemmDev p, int mtiles_alloc) {
-  extern __shared__ u32x4 lds4[];
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  int chunk = xcd + 8 * (local / p.mgroups);
-  const int mrow = local % p.mgroups;
-  if (chunk >= p.chunks) return;
-  int si = 0;
-#pragma unroll
-  for (int i = 1; i < kMaxBatch; ++i)
-    if (i < p.nseg && chunk >= p.seg[i - 1].chunk_end) si = i;
-  if (si > 0) chunk -= p.seg[si - 1].chunk_end;
-  GemmSeg sg;
-  sg.wS = p.seg[si].wS; sg.wq = p.seg[si].wq; sg.sz = p.seg[si].sz; sg.out = p.seg[si].out;
-  sg.ldo = p.seg[si].ldo; sg.N = p.seg[si].N; sg.ntiles = p.seg[si].ntiles; sg.chunk_end = 0;
-  const int tile0 = chunk * 8;
-  const int mtile0 = mrow * 8;
-  const int ks_s = p.ks_s;                       // multiple of 4 (checked by the launcher)
-  // ring units: quantisation groups, or for the all-fp16 kernel quads of fp16 k-steps
-  const int G = BITS == 16 ? ks_s >> 2 : p.G;
-  const int n16 = BITS == 16 ? 0 : ks_s >> 1;    // fp16 stages ahead of the ring units
-  const int stages = n16 + 2 * G;
-
-  if (wave < 4) {
-    // ---------------------------------------------------------------- multiplying waves
-    const int wm = wave >> 1, wn = wave & 1;
-    floatx4 acc[4][4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) acc[j][i] = floatx4{0.f, 0.f, 0.f, 0.f};
-    const u32x4* Abase = lds4 + (wm * 4) * 64 + lane;
-    const u32x4* Bbase = lds4 + 16 * 64 + (wn * 4) * 64 + lane;
-    u32x4 a[2][4], b[2][4];
-    auto request = [&](int buf_off, int t, int set) __attribute__((always_inline)) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        a[set][i] = Abase[buf_off + (t * 8 + i) * 64];
-        b[set][i] = Bbase[buf_off + (t * 8 + i) * 64];
-      }
-    };
-    int cur = 0, nxt = kLdsBufU4, nxt2 = 2 * kLdsBufU4;
-    __syncthreads();                                   // stages 0 and 1 are in buffers 0 and 1
-    request(cur, 0, 0);
-    for (int s = 0; s < stages; ++s) {
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        // fragments of the next k-step (of the next stage after the last one: its buffer was
-        // complete at the previous barrier) are requested before this k-step's MFMAs
-        if (t == 0) request(cur, 1, 1);
-        else request(nxt, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            acc[j][i] = mfma16(__builtin_bit_cast(half8, a[t][i]), __builtin_bit_cast(half8, b[t][j]), acc[j][i]);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      __syncthreads();
-      const int o = cur; cur = nxt; nxt = nxt2; nxt2 = o;
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const floatx4 v = acc[j][i];
-        if (mtile0 + wm * 4 + i < mtiles_alloc)      // row tiles past the activation buffer do not exist
-          store_fragment(p, sg, make_float4(v[0], v[1], v[2], v[3]), mtile0 + wm * 4 + i,
-                         tile0 + wn * 4 + j, lane);
-      }
-    return;
-  }
-
-  // -------------------------------------------------------------------- feeding waves
-  // Load addresses are clamped instead of predicated and the full rounds are branch-free,
-  // so the only waits in the loop are for loads issued PD units earlier.
-  const int pw = wave - 4;
-  constexpr int PD = 3;
-  // One unit in registers.  A fragment ra[i]: k-step i >> 1 of the unit, row tile pw + 4 (i & 1).
-  // All-fp16 kernel: B fragment w[i]: k-step i >> 1, channel tile 2 pw + (i & 1).
-  // Low-bit kernels: w[4 j .. 4 j + 3] the code words of channel tile 2 pw + j, sz[j] its scale|zero.
-  struct Slot { u32x4 ra[8]; uint32_t w[BITS == 16 ? 32 : 8]; uint32_t sz[2]; };
-
-  // row tiles past the activation buffer are read from its last tile and never stored
-  const u32x4* abase[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    int mtile = mtile0 + pw + 4 * j;
-    mtile = mtile < mtiles_alloc ? mtile : mtiles_alloc - 1;
-    abase[j] = reinterpret_cast<const u32x4*>(p.xf) +
-               (static_cast<size_t>(mtile >> 2) * p.KS * 4 + (mtile & 3)) * 64 + lane;
-  }
-  const u32x4* wS4 = reinterpret_cast<const u32x4*>(sg.wS);
-  // unit g (clamped to the last one): k-steps kbase + 4 g .. + 3
-  const int kbase = BITS == 16 ? 0 : ks_s;
-  auto load_unit = [&](int g, Slot& sl) __attribute__((always_inline)) {
-    g = g < G ? g : G - 1;
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      sl.ra[i] = abase[i & 1][static_cast<size_t>(kbase + 4 * g + (i >> 1)) * 256];
-    if constexpr (BITS == 16) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const u32x4 v = wS4[(static_cast<size_t>(tile0 + 2 * pw + (i & 1)) * ks_s + 4 * g + (i >> 1)) * 64 + lane];
-        sl.w[4 * i] = v.x; sl.w[4 * i + 1] = v.y; sl.w[4 * i + 2] = v.z; sl.w[4 * i + 3] = v.w;
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const size_t fi = (static_cast<size_t>(tile0 + 2 * pw + j) * G + g) * 64 + lane;
-        if (BITS == 4) {
-          const u32x4 c = reinterpret_cast<const u32x4*>(sg.wq)[fi];
-          sl.w[4 * j] = c.x; sl.w[4 * j + 1] = c.y; sl.w[4 * j + 2] = c.z; sl.w[4 * j + 3] = c.w;
-        } else {
-          const Code3 c = reinterpret_cast<const Code3*>(sg.wq)[fi];
-          sl.w[4 * j] = c.lo01; sl.w[4 * j + 1] = c.lo23; sl.w[4 * j + 2] = c.hi; sl.w[4 * j + 3] = 0;
-        }
-        sl.sz[j] = sg.sz[(static_cast<size_t>(tile0 + 2 * pw + j) * G + g) * 16 + (lane & 15)];
-      }
-    }
-  };
-  // half h (k-steps 2 h, 2 h + 1) of a unit into the buffer of stage s
-  auto stage_half = [&](const Slot& sl, int h, int s) __attribute__((always_inline)) {
-    u32x4* A = lds4 + (s % 3) * kLdsBufU4;
-    u32x4* Bm = A + 16 * 64;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) A[((i >> 1) * 8 + pw + 4 * (i & 1)) * 64 + lane] = sl.ra[4 * h + i];
-    if constexpr (BITS == 16) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int ii = 4 * h + i;
-        const u32x4 v = {sl.w[4 * ii], sl.w[4 * ii + 1], sl.w[4 * ii + 2], sl.w[4 * ii + 3]};
-        Bm[((i >> 1) * 8 + 2 * pw + (i & 1)) * 64 + lane] = v;
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const half2v sz2 = as_h2(sl.sz[j]);
-        const _Float16 sc = sz2.x, z = sz2.y;
-        const _Float16 clo = -(z + (_Float16)1024.0f);
-        const _Float16 chi = -(z + (_Float16)64.0f);
-        const half2v c_lo = {clo, clo}, c_hi = {chi, chi};
-        const half8 sc8 = {sc, sc, sc, sc, sc, sc, sc, sc};
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const int t4 = 2 * h + t;
-          half8 w;
-          if (BITS == 4) w = dequant4(sl.w[4 * j + t4], c_lo, c_hi);
-          else w = dequant3(sl.w[4 * j + (t4 >> 1)], sl.w[4 * j + 2], t4, c_lo);
-          w = w * sc8;                                   // (q - z) is exact, one rounding here
-          Bm[(t * 8 + 2 * pw + j) * 64 + lane] = __builtin_bit_cast(u32x4, w);
-        }
-      }
-    }
-  };
-  // fp16 stage s of a low-bit layer's salient prefix (k-steps 2 s, 2 s + 1): loads not hidden
-  auto fill16 = [&](int s) __attribute__((always_inline)) {
-    u32x4* A = lds4 + (s % 3) * kLdsBufU4;
-    u32x4* Bm = A + 16 * 64;
-    u32x4 h[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) h[i] = abase[i & 1][static_cast<size_t>(2 * s + (i >> 1)) * 256];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) A[((i >> 1) * 8 + pw + 4 * (i & 1)) * 64 + lane] = h[i];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      h[i] = wS4[(static_cast<size_t>(tile0 + 2 * pw + (i & 1)) * ks_s + 2 * s + (i >> 1)) * 64 + lane];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) Bm[((i >> 1) * 8 + 2 * pw + (i & 1)) * 64 + lane] = h[i];
-  };
-
-  Slot r0, r1, r2, r3;          // separate objects: each is promoted to registers on its own
-#define slot_(I) pick4<(I)>(r0, r1, r2, r3)
-  int steps = 0;                // barriers after the first one; must reach `stages`
-  if (G > 0) {
-    static_for<0, PD>([&](auto dc) __attribute__((always_inline)) {
-      constexpr int d = decltype(dc)::value;
-      load_unit(d, slot_(d));
-    });
-  }
-  // stages 0 and 1: two fp16 stages (n16 is even) or both halves of unit 0
-  int g0 = 0;                   // first unit not yet staged
-  if (n16 > 0) {
-    fill16(0);
-    fill16(1);
-  } else if (G > 0) {
-    stage_half(slot_(0), 0, 0);
-    stage_half(slot_(0), 1, 1);
-    load_unit(PD, slot_(0));
-    g0 = 1;
-  }
-  __syncthreads();
-  for (int s = 2; s < n16; ++s) {
-    fill16(s);
-    __syncthreads();
-    ++steps;
-  }
-  // a step pair stages unit g (slot g % PD) and refills the slot with unit g + PD
-  int g = 0;
-  if (g0 > 0) {                 // first round: unit 0 is already staged
-    static_for<1, PD>([&](auto dc) __attribute__((always_inline)) {
-      constexpr int d = decltype(dc)::value;
-      if (d < G) {
-        stage_half(slot_(d), 0, n16 + 2 * d);
-        __syncthreads();
-        stage_half(slot_(d), 1, n16 + 2 * d + 1);
-        load_unit(d + PD, slot_(d));
-        __syncthreads();
-        steps += 2;
-      }
-    });
-    g = PD;
-  }
-  for (; g + PD <= G; g += PD) {
-    static_for<0, PD>([&](auto dc) __attribute__((always_inline)) {
-      constexpr int d = decltype(dc)::value;
-      stage_half(slot_(d), 0, n16 + 2 * (g + d));
-      __syncthreads();
-      stage_half(slot_(d), 1, n16 + 2 * (g + d) + 1);
-      load_unit(g + d + PD, slot_(d));
-      __syncthreads();
-      steps += 2;
-    });
-  }
-  static_for<0, PD>([&](auto dc) __attribute__((always_inline)) {
-    constexpr int d = decltype(dc)::value;
-    if (g + d < G) {
-      stage_half(slot_(d), 0, n16 + 2 * (g + d));
-      __syncthreads();
-      stage_half(slot_(d), 1, n16 + 2 * (g + d) + 1);
-      __syncthreads();
-      steps += 2;
-    }
-  });
-#undef slot_
-  // the last stages have nothing left to stage behind them
-  for (; steps < stages; ++steps) __syncthreads();
-}
-
 // xhat fragments from x by a column permutation (or identity): the prologue of
 // the rotation-less layer and of the dense rotation.  Storage order keeps channels
 // ascending inside the salient and inside the remaining part, so most 8-channel
@@ -897,7 +643,7 @@ static int hip_fail(hipError_t e, const char* what) {
 
 template <int BITS, int MT, int NT, int WPB, int DEPTH>
 static int launch_gemm_t(const GemmDev& d, hipStream_t st) {
-  const int xblocks = ((d.chunks + 7) / 8) * 8 * d.mgroups;
+  const int xblocks = map_grid(d.chunks, d.mgroups);
   hipLaunchKernelGGL((gemm_kernel<BITS, MT, NT, WPB, DEPTH>), dim3(xblocks), dim3(WPB * 64), 0, st, d);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "gemm_kernel launch");
@@ -1007,38 +753,6 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
   d.mgroups = ((a.M + 15) / 16 + sh.mt - 1) / sh.mt;
   const int bits = a.G == 0 ? 16 : a.bits;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  // very large M (prefill-sized calls): LDS-tiled 128 x 128 kernel
-  {
-    const int chunks128 = ntiles_total / 8, mrows = (a.M + 127) / 128;
-    const bool fits = a.ks_s % 4 == 0 && a.xrow == nullptr;
-    // measured cross-over against the register-tiled kernel: between M = 1024 and M = 2048
-    const bool want = tune.lds == 1 || (tune.lds == 0 && a.M >= 2048 && chunks128 * mrows >= 256);
-    if (fits && want) {
-      int c = 0;
-      for (int i = 0; i < kMaxBatch; ++i) {
-        if (i < a.nseg) c += a.seg[i].ntiles / 8;
-        d.seg[i].chunk_end = c;
-      }
-      d.chunks = c;
-      d.mgroups = mrows;
-      const int xblocks = ((d.chunks + 7) / 8) * 8 * d.mgroups;
-      const int mtiles_alloc = ((a.M + kMBlock - 1) / kMBlock) * 4;
-      const size_t lds = kLdsKernelBytes;
-      hipError_t e = hipSuccess;
-#define ROSAQ_LDS(B)                                                                          \
-      if (bits == B) {                                                                          \
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_lds_kernel<B>),              \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)); \
-        if (e == hipSuccess) {                                                                  \
-          hipLaunchKernelGGL((gemm_lds_kernel<B>), dim3(xblocks), dim3(512), lds, st, d, mtiles_alloc); \
-          e = hipGetLastError();                                                                \
-        }                                                                                       \
-      }
-      ROSAQ_LDS(4) ROSAQ_LDS(3) ROSAQ_LDS(16)
-#undef ROSAQ_LDS
-      return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "gemm_lds_kernel launch");
-    }
-  }
 #define ROSAQ_CASE(B, MT_, NT_, W)                                              \
   if (bits == B && sh.mt == MT_ && sh.nt == NT_ && sh.wpb == W) {              \
     if (sh.depth == 1) return launch_gemm_t<B, MT_, NT_, W, 1>(d, st);           \

@@ -276,32 +276,25 @@ def test_pca_headwise_on_gpu_against_oracle(D, n_cal):
 
 
 @pytest.mark.parametrize("mode,bits,M,D,N,K", [(O.MODE_HEADWISE, 4, 256, 512, 384, 128), (O.MODE_NONE, 3, 130, 384, 200, 128),
-                                               (O.MODE_FULL, 4, 200, 256, 256, 0), (O.MODE_HEADWISE, 4, 128, 256, 130, 256),
-                                               (O.MODE_FULL, 4, 200, 1024, 256, 0), (O.MODE_HEADWISE, 3, 136, 2048, 144, 128)])
-def test_large_m_lds_kernel(mode, bits, M, D, N, K):
-    """The 128 x 128 LDS-tiled kernel (forced here; picked automatically for large launches),
-    including ragged M and N, an all-fp16 layer, no salient channels, contractions long enough for
-    several rounds of the feeding waves' register ring, and the dense rotation written in fragment order."""
-    print(f"case lds mode={mode} bits={bits} M={M} D={D} N={N} K={K}", flush=True)
+                                               (O.MODE_FULL, 4, 200, 1024, 256, 0), (O.MODE_HEADWISE, 3, 520, 256, 144, 128)])
+def test_many_row_groups(mode, bits, M, D, N, K):
+    """More than four row groups per channel chunk: the workgroups of an XCD are laid out in blocks of
+    8 chunks x 4 row groups; ragged M and N."""
+    print(f"case rows mode={mode} bits={bits} M={M} D={D} N={N} K={K}", flush=True)
     lay, Q, lam = make_case(300 + M, M, D, N, 300, mode)
     ref = O.pack(lay["W"], Q, lam, K, bits, mode)
     p = B.rosaq_pack_weights(lay["W"], Q, lam, K, bits, mode)
-    B.rosaq_tune("lds", 1)
-    try:
-        y1 = run_gpu(p, lay["x"])
-    finally:
-        B.rosaq_tune("lds", 2)
-    try:
-        y0 = run_gpu(p, lay["x"])
-    finally:
-        B.rosaq_tune("lds", 0)
-    check_output(y1, lay["x"], Q, ref)
-    check_output(y0, lay["x"], Q, ref)
+    for mt in (0, 1, 2):
+        B.rosaq_tune("mt", mt)
+        try:
+            check_output(run_gpu(p, lay["x"]), lay["x"], Q, ref)
+        finally:
+            B.rosaq_tune("mt", 0)
     p.free()
 
 
-def test_prefill_sized_call_default_selection():
-    """M = 2048 with 256 output tiles: the default heuristic routes this call to the LDS-tiled kernel."""
+def test_prefill_sized_call():
+    """M = 2048: 32 row groups per channel chunk."""
     M, D, N = 2048, 256, 2048
     print(f"case prefill M={M} D={D} N={N}", flush=True)
     lay, Q, lam = make_case(411, M, D, N, 300, O.MODE_HEADWISE)
