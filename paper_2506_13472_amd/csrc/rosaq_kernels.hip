@@ -119,7 +119,12 @@ struct GemmDev {
 constexpr int kMapCols = 8, kMapRows = 4;
 __device__ __forceinline__ bool map_block(int b, int chunks, int mgroups, int& chunk, int& mg) {
   const int xcd = b & 7, local = b >> 3;
-  const int tr = mgroups < kMapRows ? mgroups : kMapRows;
+  if (mgroups <= kMapRows) {                              // plain chunk-major order
+    mg = local % mgroups;
+    chunk = xcd + 8 * (local / mgroups);
+    return chunk < chunks;
+  }
+  const int tr = kMapRows;
   const int cx = (chunks + 7) >> 3;                       // chunk slots of one XCD
   const int nbc = (cx + kMapCols - 1) / kMapCols;
   const int block = local / (kMapCols * tr), inner = local - block * (kMapCols * tr);
@@ -129,7 +134,8 @@ __device__ __forceinline__ bool map_block(int b, int chunks, int mgroups, int& c
   return ci < cx && chunk < chunks && mg < mgroups;
 }
 static int map_grid(int chunks, int mgroups) {
-  const int tr = mgroups < kMapRows ? mgroups : kMapRows;
+  if (mgroups <= kMapRows) return ((chunks + 7) / 8) * 8 * mgroups;
+  const int tr = kMapRows;
   const int cx = (chunks + 7) / 8;
   const int nbc = (cx + kMapCols - 1) / kMapCols;
   return 8 * nbc * ((mgroups + tr - 1) / tr) * kMapCols * tr;
