@@ -55,26 +55,45 @@ __device__ __forceinline__ half8 dequant4(uint32_t v, half2v c_lo, half2v c_hi) 
   return half8{h0.x, h0.y, h1.x, h1.y, h2.x, h2.y, h3.x, h3.y};
 }
 
-// Eight 3-bit codes of k-step t: low two bits from the 2-bit plane dword `lo`
-// (fields 4*(t&1)+i), high bit from the 1-bit plane dword `hi` (fields 4*t+i).
-// Per fp16 pair: one shift + and-or for the low bits, one shift + and-or to drop the
-// high bit at mantissa bit 2; 0x6400 | q is 1024 + q.
-__device__ __forceinline__ half8 dequant3(uint32_t lo, uint32_t hi, int t, half2v c_lo) {
+// Eight 3-bit codes of k-step t -> eight fp16 values (q - z), exactly.  The 16 fp16 pairs
+// P = 4 t + i of a lane's group sit in three dwords: pair P < 15 in dword P / 5 at bit
+// offset 3 (P % 5) of both halves, pair 15 in the spare bits 15 / 31 (code bit b in dword b).
+// A field at offset o <= 6 is masked straight into the mantissa: 0x6400 | (q << o) is the
+// fp16 number 1024 + 2^o q, and one fma with 2^-o and -(1024 * 2^-o + z) gives q - z; the
+// fields at offsets 9 and 12 take one shared shift first.  10 instructions per k-step.
+struct Dq3 { half2v c0, c3, c6; };   // -(1024 + z), -(128 + z), -(16 + z)
+__device__ __forceinline__ Dq3 dq3_consts(_Float16 z) {
+  const _Float16 a = -(z + (_Float16)1024.0f), b = -(z + (_Float16)128.0f), c = -(z + (_Float16)16.0f);
+  return Dq3{half2v{a, a}, half2v{b, b}, half2v{c, c}};
+}
+__device__ __forceinline__ half8 dequant3(uint32_t w0, uint32_t w1, uint32_t w2, int t, const Dq3& k) {
   const uint32_t kMagic = 0x64006400u;
+  const half2v eighth = {(_Float16)0.125f, (_Float16)0.125f};
+  const half2v sixty4th = {(_Float16)0.015625f, (_Float16)0.015625f};
+  const uint32_t w[3] = {w0, w1, w2};
   half2v h[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int sl = 2 * (4 * (t & 1) + i);          // low field position
-    const int sh = 4 * t + i - 2;                  // high bit position minus its target bit 2
-    const uint32_t r = and_or(sl ? lo >> sl : lo, 0x00030003u, kMagic);
-    const uint32_t hs = sh > 0 ? hi >> sh : (sh < 0 ? hi << -sh : hi);
-    h[i] = as_h2(and_or(hs, 0x00040004u, r)) + c_lo;
+    const int P = 4 * t + i;
+    if (P < 15) {
+      const int s = P % 5;
+      const uint32_t src = s < 3 ? w[P / 5] : w[P / 5] >> 9;
+      const int o = s < 3 ? s : s - 3;
+      if (o == 0) h[i] = as_h2(and_or(src, 0x00070007u, kMagic)) + k.c0;
+      else if (o == 1) h[i] = __builtin_elementwise_fma(as_h2(and_or(src, 0x00380038u, kMagic)), eighth, k.c3);
+      else h[i] = __builtin_elementwise_fma(as_h2(and_or(src, 0x01c001c0u, kMagic)), sixty4th, k.c6);
+    } else {
+      uint32_t r = and_or(w0 >> 15, 0x00010001u, kMagic);
+      r = and_or(w1 >> 14, 0x00020002u, r);
+      r = and_or(w2 >> 13, 0x00040004u, r);
+      h[i] = as_h2(r) + k.c0;
+    }
   }
   return half8{h[0].x, h[0].y, h[1].x, h[1].y, h[2].x, h[2].y, h[3].x, h[3].y};
 }
 
 // 12-byte lane record of the INT3 image, read with one global_load_dwordx3
-struct __attribute__((aligned(4))) Code3 { uint32_t lo01, lo23, hi; };
+struct __attribute__((aligned(4))) Code3 { uint32_t w0, w1, w2; };
 
 // One packed layer inside a launch.  A launch covers up to kMaxBatch layers that
 // share the rotated input (e.g. the q, k, v projections of one attention block).
@@ -175,7 +194,8 @@ __device__ __forceinline__ void store_fragment(const GemmDev& p, const GemmSeg& 
 // Workgroups that share a channel chunk (different row tiles) are placed on one XCD
 // so that the weights are fetched from HBM once and found in that XCD's L2 after.
 template <int BITS, int MT, int NT, int WPB, int DEPTH>
-__global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) void gemm_kernel(GemmDev p) {
+__global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? (MT == 4 ? 2 : 4) : 1))
+void gemm_kernel(GemmDev p) {
   // the waves' partial tiles meet in LDS, in one pass or (large tiles) in two halves
   constexpr int kRedPasses = WPB * NT * MT > 128 ? 2 : 1;
   constexpr int kRedNT = NT / kRedPasses;
@@ -273,7 +293,7 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
         r.cw[nt][0] = c.x; r.cw[nt][1] = c.y; r.cw[nt][2] = c.z; r.cw[nt][3] = c.w;
       } else {
         const Code3 c = reinterpret_cast<const Code3*>(sg.wq)[fi];
-        r.cw[nt][0] = c.lo01; r.cw[nt][1] = c.lo23; r.cw[nt][2] = c.hi;
+        r.cw[nt][0] = c.w0; r.cw[nt][1] = c.w1; r.cw[nt][2] = c.w2;
         r.cw[nt][3] = 0;
       }
       r.sz[nt] = sg.sz[(static_cast<size_t>(wt[nt]) * p.G + g) * 16 + (lane & 15)];
@@ -306,6 +326,7 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
       const _Float16 clo = -(z + (_Float16)1024.0f);
       const _Float16 chi = -(z + (_Float16)64.0f);
       const half2v c_lo = {clo, clo}, c_hi = {chi, chi};
+      const Dq3 k3 = dq3_consts(z);
       floatx4 tmp[MT];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) tmp[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -313,7 +334,7 @@ __global__ __launch_bounds__(WPB * 64, (DEPTH == 1 && MT * NT <= 4 ? 4 : 1)) voi
       for (int t = 0; t < 4; ++t) {
         half8 b;
         if (BITS == 4) b = dequant4(r.cw[nt][t], c_lo, c_hi);
-        else b = dequant3(r.cw[nt][t >> 1], r.cw[nt][2], t, c_lo);
+        else b = dequant3(r.cw[nt][0], r.cw[nt][1], r.cw[nt][2], t, k3);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) tmp[mt] = mfma16(as_h8(r.a[t][mt]), b, tmp[mt]);
       }

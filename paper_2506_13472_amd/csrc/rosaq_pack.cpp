@@ -315,10 +315,11 @@ void build_device_image(const Canonical& c, const float* Q, DeviceImage* img) {
           }
         }
   } else {
-    // INT3 as a 2-bit plane and a 1-bit plane (3 dwords per lane and group):
-    //   dword 0: low two bits of k-steps 0,1;  dword 1: of k-steps 2,3;
-    //     field f = 4*(t & 1) + i at bits 2f (element 2i) and 16 + 2f (element 2i+1)
-    //   dword 2: high bit, field f = 4*t + i at bit f (element 2i) and 16 + f (2i+1)
+    // INT3, 32 codes of a lane and group in 3 dwords.  The 16 fp16 pairs P = 4 * ks + i
+    // (elements 2i and 2i+1 of k-step ks) are laid out for a mask-and-or extraction into an
+    // fp16 mantissa: pair P < 15 sits in dword P / 5 at bit 3 * (P % 5) (element 2i) and
+    // 16 + 3 * (P % 5) (element 2i+1); pair 15 is spread over the spare bits 15 / 31 of the
+    // three dwords, code bit b in dword b.
     img->wq.assign(static_cast<size_t>(ntiles) * G * 64 * 3, 0);
     for (int t = 0; t < ntiles; ++t)
       for (int g = 0; g < G; ++g)
@@ -327,15 +328,18 @@ void build_device_image(const Canonical& c, const float* Q, DeviceImage* img) {
           if (n >= N) continue;
           const uint8_t* q = &c.codes[static_cast<size_t>(n) * C + g * kGroup + j * 8];
           uint32_t* dst = &img->wq[((static_cast<size_t>(t) * G + g) * 64 + lane) * 3];
-          uint32_t lo[2] = {0, 0}, hi = 0;
+          uint32_t w[3] = {0, 0, 0};
           for (int ks = 0; ks < 4; ++ks)
             for (int e = 0; e < 8; ++e) {
               const uint32_t code = q[ks * kKStep + e] & 7;
-              const int i = e >> 1, half = (e & 1) * 16;
-              lo[ks >> 1] |= (code & 3u) << (half + 2 * (4 * (ks & 1) + i));
-              hi |= (code >> 2) << (half + 4 * ks + i);
+              const int P = 4 * ks + (e >> 1), half = (e & 1) * 16;
+              if (P < 15) {
+                w[P / 5] |= code << (half + 3 * (P % 5));
+              } else {
+                for (int b = 0; b < 3; ++b) w[b] |= ((code >> b) & 1u) << (half + 15);
+              }
             }
-          dst[0] = lo[0]; dst[1] = lo[1]; dst[2] = hi;
+          dst[0] = w[0]; dst[1] = w[1]; dst[2] = w[2];
         }
   }
 
