@@ -13,7 +13,6 @@
 // fetches a fragment with one global_load_dwordx4 per lane, 1 KiB contiguous.
 #include <hip/hip_runtime.h>
 
-
 #include <algorithm>
 #include <cmath>
 
