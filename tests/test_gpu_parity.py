@@ -293,6 +293,24 @@ def test_many_row_groups(mode, bits, M, D, N, K):
     p.free()
 
 
+def test_batch_with_many_row_groups():
+    """Three layers in one launch at M = 300 (five row groups of 64): segment lookup and block order together."""
+    from paper_2506_13472_amd import torch_glue as T
+    print("case batch rows", flush=True)
+    M, D = 300, 512
+    lay, Q, lam = make_case(23, M, D, 200, 300, O.MODE_HEADWISE)
+    Ws = [lay["W"], synth.make_weight(33, 96, D), synth.make_weight(34, 330, D)]
+    refs = [O.pack(W, Q, lam, 128, 4, O.MODE_HEADWISE) for W in Ws]
+    ps = [B.rosaq_pack_weights(W, Q, lam, 128, 4, B.Q_HEADWISE) for W in Ws]
+    ys = T.linear_batch(ps, torch.from_numpy(lay["x"]).cuda())
+    torch.cuda.synchronize()
+    for y, p, ref in zip(ys, ps, refs):
+        yh = y.cpu().numpy()
+        check_output(yh, lay["x"], Q, ref)
+        assert np.array_equal(run_gpu(p, lay["x"]).view(np.uint16), yh.view(np.uint16))
+        p.free()
+
+
 def test_prefill_sized_call():
     """M = 2048: 32 row groups per channel chunk."""
     M, D, N = 2048, 256, 2048
