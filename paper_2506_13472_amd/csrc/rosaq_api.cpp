@@ -86,8 +86,9 @@ static int check_desc(const rosaq_pack_desc* d) {
     }                                                                           \
   } while (0)
 
-// What = fp16(W Q) for a dense rotation on the GPU (fp64 FMA chain per output): the host
-// version of the same product takes tens of seconds at D >= 4096.
+// What = fp16(W Q) on the GPU (fp64 FMA chain per output), dense or block-diagonal Q: the
+// host version of the dense product takes tens of seconds at D >= 4096, of the head-wise one
+// a few tenths of a second per 4096 x 4096 layer.
 static int rotate_on_device(const rosaq_pack_desc& d, hipStream_t st, std::vector<uint16_t>* out) {
   const size_t N = d.out_features, D = d.in_features;
   void *dW = nullptr, *dQ = nullptr, *dO = nullptr;
@@ -100,12 +101,14 @@ static int rotate_on_device(const rosaq_pack_desc& d, hipStream_t st, std::vecto
   }
   out->resize(N * D);
   hipError_t e = hipMalloc(&dW, N * D * 2);
-  if (e == hipSuccess) e = hipMalloc(&dQ, D * D * 4);
+  const bool headwise = d.q_mode == ROSAQ_Q_HEADWISE;
+  const size_t q_bytes = (headwise ? D * kHeadDim : D * D) * 4;
+  if (e == hipSuccess) e = hipMalloc(&dQ, q_bytes);
   if (e == hipSuccess) e = hipMalloc(&dO, N * D * 2);
   if (e == hipSuccess) e = hipMemcpyAsync(dW, wsrc, N * D * 2, hipMemcpyHostToDevice, st);
-  if (e == hipSuccess) e = hipMemcpyAsync(dQ, d.Q, D * D * 4, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess) e = hipMemcpyAsync(dQ, d.Q, q_bytes, hipMemcpyHostToDevice, st);
   int rc = ROSAQ_OK;
-  if (e == hipSuccess) rc = launch_rotate_weights_f64(dW, dQ, dO, static_cast<int>(N), static_cast<int>(D), st);
+  if (e == hipSuccess) rc = launch_rotate_weights_f64(dW, dQ, dO, static_cast<int>(N), static_cast<int>(D), headwise ? 1 : 0, st);
   if (e == hipSuccess && rc == ROSAQ_OK)
     e = hipMemcpyAsync(out->data(), dO, N * D * 2, hipMemcpyDeviceToHost, st);
   if (e == hipSuccess && rc == ROSAQ_OK) e = hipStreamSynchronize(st);
@@ -261,7 +264,12 @@ int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_pack
   std::string err;
   try {
     std::vector<uint16_t> rotated;
-    const bool on_device = !desc->host_only && desc->q_mode == ROSAQ_Q_FULL && desc->in_features >= 1024;
+    // small layers stay on the host (the transfer costs more than the product)
+    const bool on_device =
+        !desc->host_only &&
+        ((desc->q_mode == ROSAQ_Q_FULL && desc->in_features >= 1024) ||
+         (desc->q_mode == ROSAQ_Q_HEADWISE &&
+          static_cast<int64_t>(desc->out_features) * desc->in_features >= (1 << 20)));
     if (on_device) {
       // the packer validates Q and W before it uses the rotated matrix
       rc = rotate_on_device(*desc, static_cast<hipStream_t>(hip_stream), &rotated);

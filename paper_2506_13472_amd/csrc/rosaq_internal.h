@@ -81,7 +81,7 @@ int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void*
                            const int32_t* pos_dev, void* xf, void* stream);
 
 int launch_rotate_weights_f64(const void* W_dev, const void* Q_dev, void* out_dev, int N, int D,
-                              void* stream);
+                              int headwise, void* stream);
 int launch_stream_probe(const void* src, const void* shared, int workgroups, int threads, int w_kib,
                         int x_kib, int shared_kib, void* sink, void* stream);
 

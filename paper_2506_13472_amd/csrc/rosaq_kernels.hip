@@ -619,24 +619,30 @@ __device__ __forceinline__ uint16_t f64_to_f16_bits(double v) {
   return sign | static_cast<uint16_t>(((e + 15) << 10) + (static_cast<int>(m) - 1024));
 }
 
-// out[n][c] = fp16( sum_k W[n][k] * Q[k][c] ), W fp16 [N x D], Q fp32 [D x D], fp64 FMA chain
-// in increasing k.  64 x 64 outputs per workgroup, 4 x 4 per thread, 16-deep LDS tiles.
+// out[n][c] = fp16( sum_k W[n][k] * Q[k][c] ), W fp16 [N x D], fp64 FMA chain in increasing k.
+// Q fp32: dense [D x D], or (headwise) blocks [D/128][128][128] of a block-diagonal rotation,
+// where the sum runs over the 128 channels of c's head only (Eq. 5-6).
+// 64 x 64 outputs per workgroup, 4 x 4 per thread, 16-deep LDS tiles.
 __global__ __launch_bounds__(256) void rotate_weights_f64_kernel(const _Float16* __restrict__ W,
                                                                  const float* __restrict__ Q,
                                                                  uint16_t* __restrict__ out, int N,
-                                                                 int D) {
+                                                                 int D, int headwise) {
   __shared__ double sa[16][64 + 1];   // [k][row]
   __shared__ double sb[16][64];       // [k][col]
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   const int n0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int kb = headwise ? (c0 / kHeadDim) * kHeadDim : 0;      // first channel of the sum
+  const int ke = headwise ? kb + kHeadDim : D;
   double acc[4][4] = {};
-  for (int k0 = 0; k0 < D; k0 += 16) {
+  for (int k0 = kb; k0 < ke; k0 += 16) {
     for (int i = threadIdx.x; i < 64 * 16; i += 256) {
       const int r = i >> 4, k = i & 15;
       const int n = n0 + r;
       sa[k][r] = n < N ? static_cast<double>(W[static_cast<size_t>(n) * D + k0 + k]) : 0.0;
       const int kk = i >> 6, c = i & 63;
-      sb[kk][c] = static_cast<double>(Q[static_cast<size_t>(k0 + kk) * D + c0 + c]);
+      const size_t qi = headwise ? (static_cast<size_t>(kb) + (k0 + kk - kb)) * kHeadDim + (c0 + c - kb)
+                                 : static_cast<size_t>(k0 + kk) * D + c0 + c;
+      sb[kk][c] = static_cast<double>(Q[qi]);
     }
     __syncthreads();
 #pragma unroll
@@ -811,10 +817,10 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
 }
 
 int launch_rotate_weights_f64(const void* W_dev, const void* Q_dev, void* out_dev, int N, int D,
-                              void* stream) {
+                              int headwise, void* stream) {
   hipLaunchKernelGGL(rotate_weights_f64_kernel, dim3(D / 64, (N + 63) / 64), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<const _Float16*>(W_dev),
-                     static_cast<const float*>(Q_dev), static_cast<uint16_t*>(out_dev), N, D);
+                     static_cast<const float*>(Q_dev), static_cast<uint16_t*>(out_dev), N, D, headwise);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "rotate_weights_f64_kernel launch");
 }

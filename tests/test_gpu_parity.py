@@ -240,6 +240,19 @@ def test_device_rotation_packs_the_same_bits_as_the_host_path():
     p_dev.free(); p_host.free()
 
 
+def test_headwise_device_rotation_packs_the_same_bits_as_the_host_path():
+    """Block-diagonal rotations of layers with at least 2^20 weights are multiplied in on the GPU too."""
+    print("case device rotation head-wise", flush=True)
+    lay, Q, lam = make_case(3, 4, 1024, 1030, 300, O.MODE_HEADWISE)
+    ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_HEADWISE)
+    p_dev = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_HEADWISE)
+    p_host = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_HEADWISE, host_only=True)
+    check_pack(p_dev, ref)
+    check_pack(p_host, ref)
+    check_output(run_gpu(p_dev, lay["x"]), lay["x"], Q, ref)
+    p_dev.free(); p_host.free()
+
+
 @pytest.mark.parametrize("D,n_cal", [(256, 512), (1024, 700)])
 def test_pca_headwise_on_gpu_against_oracle(D, n_cal):
     """Calibration on the GPU (second moment + Jacobi per head) against the oracle's PCA of the
