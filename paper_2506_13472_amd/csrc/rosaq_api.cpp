@@ -135,7 +135,6 @@ static int upload(rosaq_packed* p, const float* Q, hipStream_t st) {
   Part parts[] = {
       {img.wS.data(), img.wS.size() * 4, &p->d_wS},
       {img.wq.data(), img.wq.size() * 4, &p->d_wq},
-      {img.sz.data(), img.sz.size() * 4, &p->d_sz},
       {img.qf.data(), img.qf.size() * 4, &p->d_qf},
       {c.perm.data(), c.perm.size() * 4, &d_perm},
       {c.pos.data(), c.pos.size() * 4, &d_pos},
@@ -192,7 +191,7 @@ static int run_main_gemm(const rosaq_packed_t* const* ps, int count, const WsPla
   a.nseg = count;
   for (int i = 0; i < count; ++i) {
     const rosaq_packed_t* p = ps[i];
-    a.seg[i].wS = p->d_wS; a.seg[i].wq = p->d_wq; a.seg[i].sz = p->d_sz;
+    a.seg[i].wS = p->d_wS; a.seg[i].wq = p->d_wq;
     a.seg[i].out = ys[i]; a.seg[i].ldo = ldys[i]; a.seg[i].N = p->c.N;
     a.seg[i].ntiles = padded_tiles(p->c.N);
   }
@@ -222,7 +221,7 @@ static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_
     if (rc != ROSAQ_OK) return rc;
   }
   a.nseg = 1;
-  a.seg[0].wS = p->d_qf; a.seg[0].wq = nullptr; a.seg[0].sz = nullptr;
+  a.seg[0].wS = p->d_qf; a.seg[0].wq = nullptr;
   a.seg[0].out = ws + w.xf_b; a.seg[0].ldo = 0; a.seg[0].N = c.D;
   a.seg[0].ntiles = padded_tiles(c.D);
   a.M = M;
@@ -320,7 +319,7 @@ int rosaq_packed_clone(const rosaq_packed_t* src, void* hip_stream, rosaq_packed
     const ptrdiff_t shift = static_cast<char*>(p->d_blob) - static_cast<char*>(src->d_blob);
     auto move = [shift](auto*& q) { q = reinterpret_cast<std::remove_reference_t<decltype(q)>>(
                                         reinterpret_cast<char*>(q) + shift); };
-    move(p->d_wS); move(p->d_wq); move(p->d_sz); move(p->d_qf); move(p->d_perm); move(p->d_pos);
+    move(p->d_wS); move(p->d_wq); move(p->d_qf); move(p->d_perm); move(p->d_pos);
   }
   *out = p;
   return ROSAQ_OK;

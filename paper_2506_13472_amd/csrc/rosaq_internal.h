@@ -40,8 +40,9 @@ int pack_host(const rosaq_pack_desc& d, Canonical* out, std::string* err,
 // Device images (host staging copies) in the kernels' fragment order.
 struct DeviceImage {
   std::vector<uint32_t> wS;   // [ntiles][K/32][64 lanes][4 dwords]   fp16 salient fragments
-  std::vector<uint32_t> wq;   // int4: [ntiles][G][64][4]; int3: [ntiles][G][64][3]
-  std::vector<uint32_t> sz;   // [ntiles][G][16]  scale | zero << 16
+  // records [ntiles][G]: int4 [64][4] codes, int3 [64][3] codes, then [16] scale | zero << 16
+  std::vector<uint32_t> wq;
+  std::vector<uint32_t> sz;   // staging only (merged into wq)
   std::vector<uint32_t> qf;   // FULL: [D/16][D/32][64][4]; HEADWISE: [H][8][4][64][4]; fp16(Q)
 };
 void build_device_image(const Canonical& c, const float* Q, DeviceImage* img);
@@ -50,8 +51,7 @@ void build_device_image(const Canonical& c, const float* Q, DeviceImage* img);
 constexpr int kMaxBatch = 4;   // layers per launch that share one rotated input
 struct GemmSegArgs {
   const void* wS;        // fp16 fragments  [ntiles][ks_s][64]   x 16 B
-  const void* wq;        // low-bit fragments
-  const void* sz;        // scale/zero pairs
+  const void* wq;        // low-bit records: code fragment + scale/zero words
   void* out;             // y (row-major fp16) or xhat fragments
   int64_t ldo;           // leading dimension of y
   int N;                 // valid output channels
@@ -101,7 +101,6 @@ struct rosaq_packed {
   // sub-buffers inside d_blob
   void* d_wS = nullptr;
   void* d_wq = nullptr;
-  void* d_sz = nullptr;
   void* d_qf = nullptr;
   int32_t* d_perm = nullptr;
   int32_t* d_pos = nullptr;

@@ -98,8 +98,7 @@ struct __attribute__((aligned(4))) Code3 { uint32_t w0, w1, w2; };
 // share the rotated input (e.g. the q, k, v projections of one attention block).
 struct GemmSeg {
   const uint4* wS;
-  const uint32_t* wq;
-  const uint32_t* sz;
+  const uint32_t* wq;   // records: code fragment (256 / 192 dwords) + 16 scale|zero words
   _Float16* out;
   int64_t ldo;
   int N;
@@ -213,7 +212,7 @@ void gemm_kernel(GemmDev p) {
     if (i < p.nseg && chunk >= p.seg[i - 1].chunk_end) si = i;
   if (si > 0) chunk -= p.seg[si - 1].chunk_end;
   GemmSeg sg;
-  sg.wS = p.seg[si].wS; sg.wq = p.seg[si].wq; sg.sz = p.seg[si].sz; sg.out = p.seg[si].out;
+  sg.wS = p.seg[si].wS; sg.wq = p.seg[si].wq; sg.out = p.seg[si].out;
   sg.ldo = p.seg[si].ldo; sg.N = p.seg[si].N; sg.ntiles = p.seg[si].ntiles; sg.chunk_end = 0;
 #ifdef ROSAQ_PROBE_EMPTY
   if (p.M > 0) return;
@@ -282,20 +281,21 @@ void gemm_kernel(GemmDev p) {
   auto load_group = [&](int g, GroupRegs& r) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      const size_t fi = (static_cast<size_t>(wt[nt]) * p.G + g) * 64 + lane;
+      constexpr int kCodeDwords = BITS == 4 ? 256 : 192, kRecDwords = kCodeDwords + 16;
+      const uint32_t* rec = sg.wq + (static_cast<size_t>(wt[nt]) * p.G + g) * kRecDwords;
       if (BITS == 4) {
 #ifdef ROSAQ_PROBE_NO_W
-        const uint4 c = make_uint4(fi, 5, 6, 7);
+        const uint4 c = make_uint4(lane, 5, 6, 7);
 #else
-        const uint4 c = reinterpret_cast<const uint4*>(sg.wq)[fi];
+        const uint4 c = reinterpret_cast<const uint4*>(rec)[lane];
 #endif
         r.cw[nt][0] = c.x; r.cw[nt][1] = c.y; r.cw[nt][2] = c.z; r.cw[nt][3] = c.w;
       } else {
-        const Code3 c = reinterpret_cast<const Code3*>(sg.wq)[fi];
+        const Code3 c = reinterpret_cast<const Code3*>(rec)[lane];
         r.cw[nt][0] = c.w0; r.cw[nt][1] = c.w1; r.cw[nt][2] = c.w2;
         r.cw[nt][3] = 0;
       }
-      r.sz[nt] = sg.sz[(static_cast<size_t>(wt[nt]) * p.G + g) * 16 + (lane & 15)];
+      r.sz[nt] = rec[kCodeDwords + (lane & 15)];
     }
     const size_t ks0 = static_cast<size_t>(p.ks_s + 4 * g);
 #pragma unroll
@@ -779,7 +779,6 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
     if (i < a.nseg) chunks += ((sa.N + kTileN - 1) / kTileN + sh.nt - 1) / sh.nt;
     d.seg[i].wS = static_cast<const uint4*>(sa.wS);
     d.seg[i].wq = static_cast<const uint32_t*>(sa.wq);
-    d.seg[i].sz = static_cast<const uint32_t*>(sa.sz);
     d.seg[i].out = static_cast<_Float16*>(sa.out);
     d.seg[i].ldo = sa.ldo;
     d.seg[i].N = sa.N;

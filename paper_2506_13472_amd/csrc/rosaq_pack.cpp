@@ -343,6 +343,19 @@ void build_device_image(const Canonical& c, const float* Q, DeviceImage* img) {
         }
   }
 
+  // One record per (tile, group): the code fragment followed by the 16 scale|zero words,
+  // so a wave finds both in adjacent cache lines (1088 bytes INT4, 832 bytes INT3).
+  {
+    const size_t cw = c.bits == 4 ? 256 : 192, rw = cw + 16;
+    std::vector<uint32_t> rec(static_cast<size_t>(ntiles) * G * rw);
+    for (size_t r = 0; r < static_cast<size_t>(ntiles) * G; ++r) {
+      std::memcpy(&rec[r * rw], &img->wq[r * cw], cw * 4);
+      std::memcpy(&rec[r * rw + cw], &img->sz[r * 16], 16 * 4);
+    }
+    img->wq.swap(rec);
+    std::vector<uint32_t>().swap(img->sz);
+  }
+
   // fp16 rotation fragments
   img->qf.clear();
   if (c.q_mode == ROSAQ_Q_FULL) {
