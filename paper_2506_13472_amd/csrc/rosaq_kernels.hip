@@ -705,12 +705,18 @@ GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tu
       if (t < best * 0.999) { best = t; s.mt = mt; s.nt = nt; }
     }
   }
-  // A 64 x 64 tiling that needs a second, mostly empty round of workgroups (e.g. gate + up of a
-  // 7B MLP in one launch: 1376 channel tiles) runs 10 % faster as 32 x 96 tiles (eight waves, like every default shape, so the
-  // summation order of an output element stays the same).
-  if (bits != 16 && s.mt == 4 && s.nt == 4 && mtiles <= 4 && (ntiles + 3) / 4 > 256 && (ntiles + 5) / 6 <= 256) {
-    s.mt = 2;
-    s.nt = 6;
+  // A 64 x 64 tiling whose last round of 256 workgroups is mostly empty (gate + up of a 7B MLP
+  // in one launch: 344 workgroups; 13824 -> 5120 at M = 256: 320) runs 6-10 % faster as 32 x 96
+  // tiles when those fill their rounds better.  Eight waves like every default shape, so the
+  // summation order of an output element stays the same.
+  if (bits != 16 && s.mt == 4 && s.nt == 4) {
+    auto fill = [](int wgs) { return static_cast<double>(wgs) / (((wgs + 255) / 256) * 256); };
+    const int wg44 = ((ntiles + 3) / 4) * ((mtiles + 3) / 4);
+    const int wg26 = ((ntiles + 5) / 6) * ((mtiles + 1) / 2);
+    if (wg44 > 256 && fill(wg44) < 0.7 && fill(wg26) >= fill(wg44) + 0.15) {
+      s.mt = 2;
+      s.nt = 6;
+    }
   }
   if (tune.mt == 1 || tune.mt == 2 || tune.mt == 4) s.mt = tune.mt;
   if (tune.nt == 1 || tune.nt == 2 || tune.nt == 4) s.nt = tune.nt;
