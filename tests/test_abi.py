@@ -115,8 +115,13 @@ def test_call_argument_errors_on_host_only_handle():
 def test_tune_keys():
     for k in ("mt", "nt", "wpb"):
         B.rosaq_tune(k, 0)
-    assert _code(lambda: B.rosaq_tune("mt", 3)) == -3
+    assert _code(lambda: B.rosaq_tune("mt", 3)) == -3          # 48-row tiles do not exist
+    for v in (3, 6, 0):
+        B.rosaq_tune("nt", v)                                  # 48- and 96-channel tiles do
+    assert _code(lambda: B.rosaq_tune("nt", 5)) == -3
     assert _code(lambda: B.rosaq_tune("wpb", 3)) == -3
+    assert _code(lambda: B.rosaq_tune("depth", 5)) == -3
+    assert _code(lambda: B.rosaq_tune("stages", 0)) == -3
     assert _code(lambda: B.rosaq_tune("nope", 1)) == -3
 
 
