@@ -334,3 +334,39 @@ def test_prefill_sized_call():
     check_output(run_gpu(p, lay["x"]), lay["x"], Q, ref)
     p.free()
 
+
+def test_seeded_random_shapes_modes_and_tiles():
+    """A seeded sweep over M, D, N, K, bits, rotation mode and forced tile shapes (ragged everything):
+    stored arrays bit-exact, outputs within tolerance."""
+    rng = np.random.default_rng(12345)
+    tiles = [(0, 0, 0, 0), (1, 1, 8, 2), (1, 1, 16, 1), (1, 2, 8, 3), (1, 4, 8, 2), (2, 1, 8, 2), (2, 2, 8, 1),
+             (2, 2, 8, 3), (2, 4, 8, 2), (4, 1, 8, 1), (4, 2, 8, 2), (4, 4, 8, 1), (4, 4, 4, 2), (2, 4, 4, 3),
+             (4, 3, 8, 1), (2, 3, 8, 2), (2, 6, 8, 1), (2, 6, 8, 2), (4, 6, 4, 1), (1, 2, 16, 2), (2, 1, 16, 1)]
+    for it in range(32):
+        mode = int(rng.integers(0, 3))
+        bits = int(rng.choice([3, 4]))
+        D = int(rng.choice([128, 256, 384, 512, 768, 1024]))
+        K = int(rng.choice([k for k in (0, 128, 256, D) if k <= D]))
+        N = int(rng.integers(1, 700))
+        M = int(rng.choice([1, 2, 7, 16, 17, 33, 64, 65, 100, 130, 257, 300]))
+        mt, nt, wpb, depth = tiles[int(rng.integers(0, len(tiles)))]
+        print(f"case {it}: mode={mode} bits={bits} M={M} D={D} N={N} K={K} tile=({mt},{nt},{wpb},{depth})", flush=True)
+        lay = synth.make_layer(1000 + it, M, D, N, 200)
+        if mode == O.MODE_NONE:
+            Q, lam = None, np.abs(lay["X_cal"]).mean(axis=0)
+        elif mode == O.MODE_FULL:
+            Q, lam = synth.random_orthogonal_dense(it, D), synth.descending_spectrum(it + 1, D, 1)
+        else:
+            Q, lam = synth.random_orthogonal_blocks(it, D // 128), synth.descending_spectrum(it + 1, D, D // 128)
+        ref = O.pack(lay["W"], Q, lam, K, bits, mode)
+        p = B.rosaq_pack_weights(lay["W"], Q, lam, K, bits, mode)
+        check_pack(p, ref)
+        for k, v in (("mt", mt), ("nt", nt), ("wpb", wpb), ("depth", depth)):
+            B.rosaq_tune(k, v)
+        try:
+            check_output(run_gpu(p, lay["x"]), lay["x"], Q, ref)
+        finally:
+            for k in ("mt", "nt", "wpb", "depth"):
+                B.rosaq_tune(k, 0)
+            p.free()
+
