@@ -271,7 +271,8 @@ void build_device_image(const Canonical& c, const float* Q, DeviceImage* img) {
   img->wS.assign(static_cast<size_t>(ntiles) * ks_s * 64 * 4, 0);
   {
     uint16_t* h = reinterpret_cast<uint16_t*>(img->wS.data());
-    for (int t = 0; t < ntiles; ++t)
+    parallel_rows(ntiles, [&](int t_lo, int t_hi) {
+    for (int t = t_lo; t < t_hi; ++t)
       for (int ks = 0; ks < ks_s; ++ks)
         for (int lane = 0; lane < 64; ++lane) {
           const int n = t * kTileN + (lane & 15), j = lane >> 4;
@@ -280,6 +281,7 @@ void build_device_image(const Canonical& c, const float* Q, DeviceImage* img) {
           for (int e = 0; e < 8; ++e)
             dst[e] = c.W_S[static_cast<size_t>(n) * K + ks * kKStep + j * 8 + e];
         }
+    });
   }
 
   // scale | zero << 16 : [tile][g][16]
@@ -300,7 +302,8 @@ void build_device_image(const Canonical& c, const float* Q, DeviceImage* img) {
     // dword t holds k-step t; element e sits in nibble (e >> 1) + 4 * (e & 1), so
     // that (v >> 4i) & 0x000f000f is the fp16 pair (e = 2i, e = 2i + 1).
     img->wq.assign(static_cast<size_t>(ntiles) * G * 64 * 4, 0);
-    for (int t = 0; t < ntiles; ++t)
+    parallel_rows(ntiles, [&](int t_lo, int t_hi) {
+    for (int t = t_lo; t < t_hi; ++t)
       for (int g = 0; g < G; ++g)
         for (int lane = 0; lane < 64; ++lane) {
           const int n = t * kTileN + (lane & 15), j = lane >> 4;
@@ -314,6 +317,7 @@ void build_device_image(const Canonical& c, const float* Q, DeviceImage* img) {
             dst[ks] = v;
           }
         }
+    });
   } else {
     // INT3, 32 codes of a lane and group in 3 dwords.  The 16 fp16 pairs P = 4 * ks + i
     // (elements 2i and 2i+1 of k-step ks) are laid out for a mask-and-or extraction into an
@@ -321,7 +325,8 @@ void build_device_image(const Canonical& c, const float* Q, DeviceImage* img) {
     // 16 + 3 * (P % 5) (element 2i+1); pair 15 is spread over the spare bits 15 / 31 of the
     // three dwords, code bit b in dword b.
     img->wq.assign(static_cast<size_t>(ntiles) * G * 64 * 3, 0);
-    for (int t = 0; t < ntiles; ++t)
+    parallel_rows(ntiles, [&](int t_lo, int t_hi) {
+    for (int t = t_lo; t < t_hi; ++t)
       for (int g = 0; g < G; ++g)
         for (int lane = 0; lane < 64; ++lane) {
           const int n = t * kTileN + (lane & 15), j = lane >> 4;
@@ -341,6 +346,7 @@ void build_device_image(const Canonical& c, const float* Q, DeviceImage* img) {
             }
           dst[0] = w[0]; dst[1] = w[1]; dst[2] = w[2];
         }
+    });
   }
 
   // One record per (tile, group): the code fragment followed by the 16 scale|zero words,
