@@ -74,9 +74,18 @@ def cpu_baseline(seconds_target=12.0):
         if dt >= seconds_target or n >= 64:
             break
     gbs = algorithmic_bytes()["call"] * n / dt / 1e9
-    return {"value": round(gbs, 4), "unit": "GB/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{n} of the {CALLS_PER_STEP} calls of one step (oracle linear_ref, fp64 numpy), "
-                      f"{dt / n * 1e3:.1f} ms per call"}
+    out = {"value": round(gbs, 4), "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+           "sample": f"{n} of the {CALLS_PER_STEP} calls of one step (oracle linear_ref, fp64 numpy), "
+                     f"{dt / n * 1e3:.1f} ms per call"}
+    try:                                     # one more call on a single thread, for scale
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):
+            t1 = time.perf_counter()
+            O.linear_ref(x, Qb, ref)
+            out["single_thread_ms_per_call"] = round((time.perf_counter() - t1) * 1e3, 1)
+    except Exception:
+        pass
+    return out
 
 
 SWEEP_SHAPES = [
@@ -367,6 +376,7 @@ def main():
     t_pack = time.perf_counter()
     t_pca = 0.0
     handles = []
+    rot_first = None
     for layer in range(args.layers):
         rot = []
         for which in range(2):
@@ -374,6 +384,8 @@ def main():
             t0 = time.perf_counter()
             rot.append(B.rosaq_pca_headwise(xc.data_ptr(), 512, D, xc.stride(0)))
             t_pca += time.perf_counter() - t0
+        if rot_first is None:
+            rot_first = rot[0]
         for j in range(4):
             W = synth.make_weight(1000 + 4 * layer + j, N, D)
             Qb, lam = rot[0] if j < 3 else rot[1]
@@ -485,6 +497,30 @@ def main():
         fp16 = {"us_per_call": round(us16, 3),
                 "GBps": round((2 * N * D + ab["xy"]) / (us16 * 1e-6) / 1e9, 1),
                 "rosaq_speedup": round(us16 / us_call, 3), "impl": "torch.matmul fp16 (vendor GEMM)"}
+        del Ws
+        # the library's own all-fp16 path: the same layer packed with K = D (every channel salient),
+        # four calls per layer like the unbatched workload
+        h16 = [B.rosaq_pack_weights(synth.make_weight(1000, N, D), *rot_first, D, BITS, B.Q_HEADWISE)]
+        while len(h16) < n_w:
+            h16.append(B.rosaq_packed_clone(h16[0]))
+
+        def own16_step():
+            for i in range(CALLS_PER_STEP):
+                T.linear(h16[i % n_w], x, yb, ws)
+        with torch.cuda.stream(stream):
+            own16_step()
+            stream.synchronize()
+            if args.no_graph:
+                run_own = own16_step
+            else:
+                g_own = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g_own, stream=stream):
+                    own16_step()
+                run_own = g_own.replay
+        w_own, _ = timed(run_own, args.steps, args.warmup)
+        fp16["own_all_salient_us_per_call"] = round(w_own / n_calls * 1e6, 3)
+        for h in h16:
+            h.free()
 
     # ---- the memory system's own ceiling: a pure read stream of one linear's size ------
     probe = None
