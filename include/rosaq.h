@@ -86,7 +86,8 @@ typedef struct {
 } rosaq_pack_desc;
 
 /* rosaq_pack_weights - offline step of the method (Sec. 3.1-3.3, Eq. 1-3):
- *   1. What = W Q in fp64, rounded once to fp16 (HEADWISE: per 128-column block);
+ *   1. What = W Q in fp64, rounded once to fp16 (HEADWISE: per 128-column block; large layers
+ *      run this product on the GPU, with the same result);
  *   2. salient_idx = the K channels picked by select_rule (default: largest eigenvalues), ascending;
  *      storage order perm = [salient_idx ; all other channels ascending];
  *   3. W_S = What[:, salient_idx] kept as fp16;
@@ -190,7 +191,10 @@ int rosaq_stream_probe(const void* src_dev, size_t src_bytes, const void* shared
  *   "mt", "nt"  16-row / 16-channel MFMA tiles per workgroup (0 = heuristic, 1, 2, 4; nt also 3 and 6
  *             for low-bit layers with mt >= 2)
  *   "rot_mt", "rot_nt", "rot_depth"  the same three knobs for the dense-rotation launch
- *   "wpb"     waves per workgroup splitting the contraction (0 = default, 8, 16)
+ *   "wpb"     waves per workgroup splitting the contraction (0 = default, 4, 8, 16; variants that
+ *             would not fit the register file fall back to 8)
+ *   "depth"   units (a group, or four fp16 k-steps) a wave keeps in flight (0 = default, 1-4; clamped to
+ *             what the chosen tile fits without spilling)
  *   "stages"  3 = whole call (default), 1 = prologue kernels only, 2 = main GEMM only
  *             (2 reuses the rotated activations a previous call left in the workspace) */
 int rosaq_tune(const char* key, int32_t value);
