@@ -90,3 +90,21 @@ def test_7b_decode_layer_mlp_int4_gate_up_batch_and_unrotated_down():
     check_pack(p, ref)
     check_output(run_gpu(p, xd), xd, None, ref)
     p.free()
+
+
+def test_7b_attention_qkv_batch_full_size():
+    """The launch configuration the bench times: q, k, v (4096 -> 4096 each, INT4, K = 128) share one
+    head-wise rotation and go through one rosaq_linear_batch call at M = 64."""
+    from paper_2506_13472_amd import torch_glue as T
+    from test_gpu_parity import make_case
+    print("case 7B q/k/v batch full size", flush=True)
+    lay, Q, lam = make_case(1, 64, 4096, 4096, 512, O.MODE_HEADWISE, solver="lapack")
+    Ws = [lay["W"], synth.make_weight(91, 4096, 4096), synth.make_weight(92, 4096, 4096)]
+    ps = [B.rosaq_pack_weights(W, Q, lam, 128, 4, B.Q_HEADWISE) for W in Ws]
+    ys = T.linear_batch(ps, torch.from_numpy(lay["x"]).cuda())
+    torch.cuda.synchronize()
+    for W, y, p in zip(Ws, ys, ps):
+        ref = O.pack(W, Q, lam, 128, 4, O.MODE_HEADWISE)
+        check_pack(p, ref)
+        check_output(y.cpu().numpy(), lay["x"], Q, ref)
+        p.free()
