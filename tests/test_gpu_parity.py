@@ -335,6 +335,45 @@ def test_prefill_sized_call():
     p.free()
 
 
+def test_hipgraph_replays_match_eager_calls():
+    """The run-time entry points allocate nothing and record only kernel launches, so they can be
+    captured: every replay of the graph, with eager work in between, reproduces the eager bits."""
+    from paper_2506_13472_amd import torch_glue as T
+    print("case graph", flush=True)
+    M, D = 64, 512
+    lay, Q, lam = make_case(21, M, D, 200, 300, O.MODE_HEADWISE)
+    Ws = [lay["W"], synth.make_weight(31, 96, D), synth.make_weight(32, 330, D)]
+    ps = [B.rosaq_pack_weights(W, Q, lam, 128, 4, B.Q_HEADWISE) for W in Ws]
+    lam_n = np.abs(lay["X_cal"]).mean(axis=0)
+    pn = B.rosaq_pack_weights(Ws[1], None, lam_n, 128, 3, B.Q_NONE)
+    x = torch.from_numpy(lay["x"]).cuda()
+    ws = T.alloc_workspace(ps[0], M)
+    ys = [torch.zeros((M, p.N), dtype=torch.float16, device="cuda") for p in ps]
+    yn = torch.zeros((M, pn.N), dtype=torch.float16, device="cuda")
+    eager = [y.cpu().numpy().copy() for y in T.linear_batch(ps, x)] + [T.linear(pn, x).cpu().numpy().copy()]
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        def calls():
+            T.linear_batch(ps, x, ys, ws)
+            T.linear(pn, x, yn, ws)
+        calls()
+        stream.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            calls()
+        for rep in range(3):
+            for y in ys + [yn]:
+                y.zero_()
+            T.linear(ps[0], x)                       # unrelated eager work between replays
+            stream.synchronize()
+            g.replay()
+            stream.synchronize()
+            for y, e in zip(ys + [yn], eager):
+                assert np.array_equal(y.cpu().numpy().view(np.uint16), e.view(np.uint16)), rep
+    for p in ps + [pn]:
+        p.free()
+
+
 def test_seeded_random_shapes_modes_and_tiles():
     """A seeded sweep over M, D, N, K, bits, rotation mode and forced tile shapes (ragged everything):
     stored arrays bit-exact, outputs within tolerance."""
