@@ -26,6 +26,28 @@ def _run(cmd, verbose):
     subprocess.run(cmd, check=True)
 
 
+PROBES = ("EMPTY", "NO_X", "NO_W", "NO_COMPUTE", "NO_EPI", "TIMELINE")
+
+
+def build_probe(names, verbose: bool = True) -> str:
+    """A measurement variant of the library next to the real one: `gemm_kernel` compiled with
+    -DROSAQ_PROBE_<NAME> for every name given (e.g. NO_COMPUTE: loads only; TIMELINE: per-wave clock
+    stamps read back through rosaq_debug_timeline).  Results of such a library are not valid outputs.
+    Load it by pointing the environment variable ROSAQ_LIB at the returned path.  Needs a prior build()."""
+    for n in names:
+        if n not in PROBES:
+            raise ValueError(f"unknown probe {n!r}; choose from {PROBES}")
+    out = os.path.join(PKG, "librosaq_probe_" + "_".join(names) + ".so")
+    obj = os.path.join(OBJ, "rosaq_kernels.probe_" + "_".join(names) + ".o")
+    _run([hipcc(), "-x", "hip", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+          "-packed-fp32-ops", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+          *[f"-DROSAQ_PROBE_{n}" for n in names], "-c", os.path.join(CSRC, "rosaq_kernels.hip"), "-o", obj],
+         verbose)
+    others = [os.path.join(OBJ, s + ".o") for s in HOST_SOURCES + ["rosaq_pca.hip"]]
+    _run([hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-pthread", *others, obj, "-o", out], verbose)
+    return out
+
+
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
     common = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -48,5 +70,8 @@ def build(verbose: bool = True) -> str:
 
 
 if __name__ == "__main__":
+    import sys
     build()
     print("built", LIB)
+    if len(sys.argv) > 2 and sys.argv[1] == "--probe":
+        print("built", build_probe(sys.argv[2].split("+")))

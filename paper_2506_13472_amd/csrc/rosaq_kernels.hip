@@ -105,8 +105,11 @@ struct GemmSeg {
   int ntiles;        // 16-channel tiles in the weight image
   int chunk_end;     // exclusive prefix sum of channel chunks over the layers
 };
+// ROSAQ_PROBE_* macros: measurement variants of gemm_kernel (loads only, no weights, no
+// epilogue, ...), compiled into a separate library by build.py --probe; never defined in
+// the product build.
 #ifdef ROSAQ_PROBE_TIMELINE
-// probe builds only: per-wave shader-clock stamps of the last launch
+// per-wave shader-clock stamps of the last launch
 __device__ unsigned long long g_timeline[4096 * 16 * 8];
 #define ROSAQ_STAMP(i)                                                                  \
   if (lane == 0 && blockIdx.x < 4096)                                                   \
