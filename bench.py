@@ -97,6 +97,8 @@ SWEEP_SHAPES = [
     ("13B up, full 5120^2 rotation, INT4", 5120, 13824, 4, "full", (1, 16, 64, 256)),
     ("13B down, no rotation, INT4", 13824, 5120, 4, "none", (1, 16, 64, 256)),
     ("13B down, full 13824^2 rotation, INT4", 13824, 5120, 4, "full", (64,)),
+    # not one of the benchmark's configs: a large streaming launch (7B-shaped vocabulary projection)
+    ("vocab 4096->32000, no rotation, INT4", 4096, 32000, 4, "none", (1, 16, 64)),
 ]
 
 
