@@ -103,7 +103,7 @@ struct GemmSeg {
   int64_t ldo;
   int N;
   int ntiles;        // 16-channel tiles in the weight image
-  int chunk_end;     // exclusive prefix sum of channel chunks over the layers
+  int tile_end;      // exclusive prefix sum of the layers' valid channel tiles, ceil(N / 16)
 };
 // ROSAQ_PROBE_* macros: measurement variants of gemm_kernel (loads only, no weights, no
 // epilogue, ...), compiled into a separate library by build.py --probe; never defined in
@@ -161,18 +161,45 @@ static int map_grid(int chunks, int mgroups) {
   return 8 * nbc * ((mgroups + tr - 1) / tr) * kMapCols * tr;
 }
 
-// Store one accumulator fragment of row tile `mtile` (16 rows) and channel tile
-// `tile`: lane holds rows 4*(lane/16)+i, column lane%16.
-__device__ __forceinline__ void store_fragment(const GemmDev& p, const GemmSeg& sg, float4 v,
-                                               int mtile, int tile, int lane) {
+// The layers of a launch are one list of channel tiles (layer 0's valid tiles, then layer 1's,
+// ...): a chunk of NT consecutive tiles may end in one layer and go on in the next, so a
+// batch whose layers are not a multiple of NT tiles wide still fills whole chunks.  Tile T of
+// the list lies in layer `si` at local index `local`; beyond the list it maps to the tile
+// after the last layer's last one, which loads clamp and stores skip.
+__device__ __forceinline__ void locate_tile(const GemmDev& p, int T, int& si, int& local) {
+  si = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxBatch; ++i)
+    if (i < p.nseg && T >= p.seg[i - 1].tile_end) si = i;
+  local = T - (si > 0 ? p.seg[si - 1].tile_end : 0);
+}
+
+// Layer `si` of the launch, picked by compares (indexing the by-value argument with a run-time
+// index would move it to scratch memory).
+__device__ __forceinline__ GemmSeg pick_seg(const GemmDev& p, int si) {
+  GemmSeg sg = p.seg[0];
+#pragma unroll
+  for (int i = 1; i < kMaxBatch; ++i)
+    if (si == i) sg = p.seg[i];
+  return sg;
+}
+
+// Store one accumulator fragment of row tile `mtile` (16 rows) and channel tile T of the
+// launch's tile list: lane holds rows 4*(lane/16)+i, column lane%16.
+__device__ __forceinline__ void store_fragment(const GemmDev& p, float4 v, int mtile, int T, int lane) {
+  int si, tile;
+  locate_tile(p, T, si, tile);
+  const GemmSeg sg = pick_seg(p, si);
   const int n = tile * kTileN + (lane & 15);
   if (n >= sg.N) return;
   const float vv[4] = {v.x, v.y, v.z, v.w};
+  _Float16* out = sg.out;
   if (!p.out_frag) {
+    const int64_t ldo = sg.ldo;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int m = mtile * 16 + 4 * (lane >> 4) + i;
-      if (m < p.M) sg.out[static_cast<int64_t>(m) * sg.ldo + n] = static_cast<_Float16>(vv[i]);
+      if (m < p.M) out[static_cast<int64_t>(m) * ldo + n] = static_cast<_Float16>(vv[i]);
     }
   } else {
     const int ks = n >> 5, j = (n >> 3) & 3, e = n & 7;
@@ -181,7 +208,7 @@ __device__ __forceinline__ void store_fragment(const GemmDev& p, const GemmSeg& 
       const int lane2 = 4 * (lane >> 4) + i + 16 * j;
       const size_t off =
           (((static_cast<size_t>(mtile >> 2) * p.KS_out + ks) * 4 + (mtile & 3)) * 64 + lane2) * 8 + e;
-      sg.out[off] = static_cast<_Float16>(vv[i]);
+      out[off] = static_cast<_Float16>(vv[i]);
     }
   }
 }
@@ -208,25 +235,26 @@ void gemm_kernel(GemmDev p) {
   int chunk, mg;
   if (!map_block(blockIdx.x, p.chunks, p.mgroups, chunk, mg)) return;
   ROSAQ_STAMP(0)
-  // which layer of the batch this chunk belongs to (uniform over the workgroup)
-  int si = 0;
-#pragma unroll
-  for (int i = 1; i < kMaxBatch; ++i)
-    if (i < p.nseg && chunk >= p.seg[i - 1].chunk_end) si = i;
-  if (si > 0) chunk -= p.seg[si - 1].chunk_end;
-  GemmSeg sg;
-  sg.wS = p.seg[si].wS; sg.wq = p.seg[si].wq; sg.out = p.seg[si].out;
-  sg.ldo = p.seg[si].ldo; sg.N = p.seg[si].N; sg.ntiles = p.seg[si].ntiles; sg.chunk_end = 0;
 #ifdef ROSAQ_PROBE_EMPTY
   if (p.M > 0) return;
 #endif
-  const int tile0 = chunk * NT;
+  const int tile0 = chunk * NT;   // first tile of the chunk in the launch's tile list
   const int mtile0 = mg * MT;
-  // NT need not divide the layer's tile count: the last chunk re-reads the last tile for
-  // its missing ones (their results fall outside N and are not stored)
-  int wt[NT];
+  // where each of the chunk's tiles lives (uniform over the workgroup): fp16 fragments and
+  // low-bit records of tile nt start at wS_t[nt] and wq_t[nt]
+  const uint4* wS_t[NT];
+  const uint32_t* wq_t[NT];
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) wt[nt] = tile0 + nt < sg.ntiles ? tile0 + nt : sg.ntiles - 1;
+  for (int nt = 0; nt < NT; ++nt) {
+    constexpr int kRecDwordsT = (BITS == 4 ? 256 : 192) + 16;
+    int si, tile;
+    locate_tile(p, tile0 + nt, si, tile);
+    const GemmSeg sg = pick_seg(p, si);
+    const int valid = (sg.N + kTileN - 1) / kTileN;
+    if (tile >= valid) tile = valid - 1;   // past the end of the list: re-read the last tile
+    wS_t[nt] = sg.wS + static_cast<size_t>(tile) * p.ks_s * 64;
+    wq_t[nt] = sg.wq + static_cast<size_t>(tile) * p.G * kRecDwordsT;
+  }
 
   floatx4 acc[NT][MT];
 #pragma unroll
@@ -261,7 +289,7 @@ void gemm_kernel(GemmDev p) {
   auto load_step = [&](int u, StepRegs& r) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
-      r.b[nt] = sg.wS[(static_cast<size_t>(wt[nt]) * p.ks_s + u) * 64 + lane];
+      r.b[nt] = wS_t[nt][static_cast<size_t>(u) * 64 + lane];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
       r.a[mt] = row_ok ? xa[mt][static_cast<size_t>(u) * 256] : make_uint4(0, 0, 0, 0);
@@ -285,7 +313,7 @@ void gemm_kernel(GemmDev p) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       constexpr int kCodeDwords = BITS == 4 ? 256 : 192, kRecDwords = kCodeDwords + 16;
-      const uint32_t* rec = sg.wq + (static_cast<size_t>(wt[nt]) * p.G + g) * kRecDwords;
+      const uint32_t* rec = wq_t[nt] + static_cast<size_t>(g) * kRecDwords;
       if (BITS == 4) {
 #ifdef ROSAQ_PROBE_NO_W
         const uint4 c = make_uint4(lane, 5, 6, 7);
@@ -359,7 +387,7 @@ void gemm_kernel(GemmDev p) {
       for (int t = 0; t < 4; ++t) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-          r.b[t][nt] = sg.wS[(static_cast<size_t>(wt[nt]) * ks_s + 4 * qd + t) * 64 + lane];
+          r.b[t][nt] = wS_t[nt][static_cast<size_t>(4 * qd + t) * 64 + lane];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           if (p.xrow != nullptr) {
@@ -449,7 +477,7 @@ void gemm_kernel(GemmDev p) {
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) t += acc[nt][mt][0] + acc[nt][mt][1] + acc[nt][mt][2] + acc[nt][mt][3];
-    if (t == 12345.678f) sg.out[lane] = static_cast<_Float16>(t);
+    if (t == 12345.678f) p.seg[0].out[lane] = static_cast<_Float16>(t);
     return;
   }
 #endif
@@ -475,7 +503,7 @@ void gemm_kernel(GemmDev p) {
         const float4 o = red[w][slot][lane];
         v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
       }
-      store_fragment(p, sg, v, mtile0 + slot % MT, tile0 + pass * kRedNT + slot / MT, lane);
+      store_fragment(p, v, mtile0 + slot % MT, tile0 + pass * kRedNT + slot / MT, lane);
     }
   }
   ROSAQ_STAMP(4)
@@ -699,7 +727,7 @@ GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tu
   for (int mt = 1; mt <= 4; mt <<= 1) {
     if (mt > 1 && mt / 2 >= mtiles) break;           // do not pad rows beyond the next tile size
     for (int nt = 1; nt <= 4; nt <<= 1) {
-      const double tiles = static_cast<double>(ntiles / nt) * ((mtiles + mt - 1) / mt);
+      const double tiles = static_cast<double>((ntiles + nt - 1) / nt) * ((mtiles + mt - 1) / mt);
       const double rounds = std::ceil(tiles / 256.0);
       const double inflow = (mt * 16 * k * 2.0 + nt * 16 * k * wbytes) / 120e3;
       const double valu = bits == 16 ? 0.0 : nt * k * (bits == 3 ? 2.9e-4 : 1.7e-4) + mt * nt * k * 1.3e-5;
@@ -708,15 +736,19 @@ GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tu
       if (t < best * 0.999) { best = t; s.mt = mt; s.nt = nt; }
     }
   }
-  // A 64 x 64 tiling whose last round of 256 workgroups is mostly empty (gate + up of a 7B MLP
-  // in one launch: 344 workgroups; 13824 -> 5120 at M = 256: 320) runs 6-10 % faster as 32 x 96
-  // tiles when those fill their rounds better.  Eight waves like every default shape, so the
-  // summation order of an output element stays the same.
+  // 64 x 64 against 32 x 96 tiles when the launch is one or two rounds of 256 workgroups long.
+  // What a workgroup has to pull through its CU's vector-memory path decides (rows of the
+  // rotated activations plus its weights; 32 x 96 dequantises every weight twice, priced at
+  // 10 %): q/k/v of a 7B attention block in one launch are 192 workgroups of 64 x 64 but exactly
+  // 256 of 32 x 96 (13.8 against 16.3 us); gate + up of a 7B MLP 344 against 460 (25.4 against
+  // 28.3 us).  Eight waves like every default shape, so the summation order stays the same.
   if (bits != 16 && s.mt == 4 && s.nt == 4) {
-    auto fill = [](int wgs) { return static_cast<double>(wgs) / (((wgs + 255) / 256) * 256); };
+    auto rounds = [](int wgs) { return (wgs + 255) / 256; };
     const int wg44 = ((ntiles + 3) / 4) * ((mtiles + 3) / 4);
     const int wg26 = ((ntiles + 5) / 6) * ((mtiles + 1) / 2);
-    if (wg44 > 256 && fill(wg44) < 0.7 && fill(wg26) >= fill(wg44) + 0.15) {
+    const double cost44 = rounds(wg44) * (64 * 2.0 + 64 * wbytes);
+    const double cost26 = rounds(wg26) * (32 * 2.0 + 96 * wbytes) * 1.1;
+    if (rounds(wg44) <= 2 && cost26 < cost44) {
       s.mt = 2;
       s.nt = 6;
     }
@@ -778,23 +810,23 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
   d.ldx = a.ldx;
   d.M = a.M; d.ks_s = a.ks_s; d.G = a.G; d.KS = a.KS; d.KS_out = a.KS_out;
   d.out_frag = a.out_frag;
-  int ntiles_total = 0;
-  for (int i = 0; i < a.nseg; ++i) ntiles_total += a.seg[i].ntiles;
-  const GemmShape sh = pick_gemm_shape(a.M, ntiles_total, a.KS * kKStep, a.G == 0 ? 16 : a.bits, tune);
+  int tiles_total = 0;
+  for (int i = 0; i < a.nseg; ++i) tiles_total += (a.seg[i].N + kTileN - 1) / kTileN;
+  const GemmShape sh = pick_gemm_shape(a.M, tiles_total, a.KS * kKStep, a.G == 0 ? 16 : a.bits, tune);
   d.nseg = a.nseg;
-  int chunks = 0;
+  int tiles = 0;   // valid channel tiles of all layers, in launch order
   for (int i = 0; i < kMaxBatch; ++i) {
     const GemmSegArgs& sa = a.seg[i < a.nseg ? i : 0];
-    if (i < a.nseg) chunks += ((sa.N + kTileN - 1) / kTileN + sh.nt - 1) / sh.nt;
+    if (i < a.nseg) tiles += (sa.N + kTileN - 1) / kTileN;
     d.seg[i].wS = static_cast<const uint4*>(sa.wS);
     d.seg[i].wq = static_cast<const uint32_t*>(sa.wq);
     d.seg[i].out = static_cast<_Float16*>(sa.out);
     d.seg[i].ldo = sa.ldo;
     d.seg[i].N = sa.N;
     d.seg[i].ntiles = sa.ntiles;
-    d.seg[i].chunk_end = chunks;
+    d.seg[i].tile_end = tiles;
   }
-  d.chunks = chunks;
+  d.chunks = (tiles + sh.nt - 1) / sh.nt;
   d.mgroups = ((a.M + 15) / 16 + sh.mt - 1) / sh.mt;
   const int bits = a.G == 0 ? 16 : a.bits;
   hipStream_t st = static_cast<hipStream_t>(stream);

@@ -136,6 +136,39 @@ def test_batch_of_layers_sharing_the_rotation(mode, bits):
         p.free()
 
 
+@pytest.mark.parametrize("mt,nt,wpb", [(1, 2, 8), (2, 4, 8), (4, 4, 8), (2, 3, 8), (4, 3, 8), (2, 6, 8), (4, 6, 4)])
+@pytest.mark.parametrize("bits", [4, 3])
+def test_chunks_that_span_the_layers_of_a_batch(mt, nt, wpb, bits):
+    """Layers of 13, 6, 21 and 1 channel tiles in one launch: with every tile width some chunk
+    ends in one layer and goes on in the next, and the last chunk runs past the end of the list."""
+    from paper_2506_13472_amd import torch_glue as T
+    print(f"case spanning chunks mt={mt} nt={nt} wpb={wpb} bits={bits}", flush=True)
+    M, D = 50, 640
+    lay, Q, lam = make_case(41, M, D, 200, 300, O.MODE_HEADWISE)
+    Ws = [lay["W"], synth.make_weight(51, 96, D), synth.make_weight(52, 330, D), synth.make_weight(53, 9, D)]
+    refs = [O.pack(W, Q, lam, 128, bits, O.MODE_HEADWISE) for W in Ws]
+    ps = [B.rosaq_pack_weights(W, Q, lam, 128, bits, B.Q_HEADWISE) for W in Ws]
+    x = torch.from_numpy(lay["x"]).cuda()
+    singles = [run_gpu(p, lay["x"]) for p in ps]          # default tiles, one layer per launch
+    for k, v in (("mt", mt), ("nt", nt), ("wpb", wpb)):
+        B.rosaq_tune(k, v)
+    try:
+        ys = [torch.full((M, W.shape[0] + 3), 5.0, dtype=torch.float16, device="cuda") for W in Ws]
+        T.linear_batch(ps, x, [y[:, :W.shape[0]] for y, W in zip(ys, Ws)])
+        torch.cuda.synchronize()
+    finally:
+        for k in ("mt", "nt", "wpb"):
+            B.rosaq_tune(k, 0)
+    for y, W, ref, single in zip(ys, Ws, refs, singles):
+        yh = y.cpu().numpy()
+        assert np.all(yh[:, W.shape[0]:] == 5.0)          # nothing written past a layer's last channel
+        check_output(yh[:, :W.shape[0]], lay["x"], Q, ref)
+        if wpb == 8:                                       # same wave count, same summation order
+            assert np.array_equal(yh[:, :W.shape[0]].view(np.uint16), single.view(np.uint16))
+    for p in ps:
+        p.free()
+
+
 def test_strided_x_and_y():
     from paper_2506_13472_amd import torch_glue as T
     print("case strided", flush=True)
