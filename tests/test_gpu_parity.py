@@ -442,3 +442,46 @@ def test_seeded_random_shapes_modes_and_tiles():
                 B.rosaq_tune(k, 0)
             p.free()
 
+
+
+def test_seeded_random_batches_and_tiles():
+    """A seeded sweep over batches of 2-4 layers of random widths, with forced tile shapes: every layer of
+    the launch within tolerance of the oracle, nothing written outside a layer's output."""
+    from paper_2506_13472_amd import torch_glue as T
+    rng = np.random.default_rng(777)
+    tiles = [(0, 0, 0, 0), (1, 1, 8, 2), (1, 2, 8, 2), (1, 4, 8, 2), (2, 2, 8, 1), (2, 4, 8, 2), (4, 2, 8, 2),
+             (4, 4, 8, 1), (4, 3, 8, 1), (2, 3, 8, 2), (2, 6, 8, 1), (4, 6, 4, 1), (1, 1, 16, 1), (4, 4, 4, 2)]
+    for it in range(20):
+        mode = int(rng.integers(0, 3))
+        bits = int(rng.choice([3, 4]))
+        D = int(rng.choice([256, 384, 512, 768]))
+        K = int(rng.choice([0, 128, 256]))
+        Ns = [int(rng.integers(1, 400)) for _ in range(int(rng.integers(2, 5)))]
+        M = int(rng.choice([1, 5, 16, 31, 64, 70, 129, 260]))
+        mt, nt, wpb, depth = tiles[int(rng.integers(0, len(tiles)))]
+        print(f"case {it}: mode={mode} bits={bits} M={M} D={D} Ns={Ns} K={K} tile=({mt},{nt},{wpb},{depth})", flush=True)
+        x = synth.make_activations(3000 + it, M, D)
+        if mode == O.MODE_NONE:
+            Q, lam = None, synth.descending_spectrum(it + 1, D, 1)
+        elif mode == O.MODE_FULL:
+            Q, lam = synth.random_orthogonal_dense(it, D), synth.descending_spectrum(it + 1, D, 1)
+        else:
+            Q, lam = synth.random_orthogonal_blocks(it, D // 128), synth.descending_spectrum(it + 1, D, D // 128)
+        Ws = [synth.make_weight(4000 + 10 * it + i, N, D) for i, N in enumerate(Ns)]
+        refs = [O.pack(W, Q, lam, K, bits, mode) for W in Ws]
+        ps = [B.rosaq_pack_weights(W, Q, lam, K, bits, mode) for W in Ws]
+        ys = [torch.full((M, N + 5), -3.0, dtype=torch.float16, device="cuda") for N in Ns]
+        for k, v in (("mt", mt), ("nt", nt), ("wpb", wpb), ("depth", depth)):
+            B.rosaq_tune(k, v)
+        try:
+            T.linear_batch(ps, torch.from_numpy(x).cuda(), [y[:, :N] for y, N in zip(ys, Ns)])
+            torch.cuda.synchronize()
+        finally:
+            for k in ("mt", "nt", "wpb", "depth"):
+                B.rosaq_tune(k, 0)
+        for y, N, ref in zip(ys, Ns, refs):
+            yh = y.cpu().numpy()
+            assert np.all(yh[:, N:] == -3.0)
+            check_output(yh[:, :N], x, Q, ref)
+        for p in ps:
+            p.free()
