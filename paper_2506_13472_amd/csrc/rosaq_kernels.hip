@@ -736,19 +736,22 @@ GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tu
       if (t < best * 0.999) { best = t; s.mt = mt; s.nt = nt; }
     }
   }
-  // 64 x 64 against 32 x 96 tiles when the launch is one or two rounds of 256 workgroups long.
-  // What a workgroup has to pull through its CU's vector-memory path decides (rows of the
-  // rotated activations plus its weights; 32 x 96 dequantises every weight twice, priced at
-  // 10 %): q/k/v of a 7B attention block in one launch are 192 workgroups of 64 x 64 but exactly
-  // 256 of 32 x 96 (13.8 against 16.3 us); gate + up of a 7B MLP 344 against 460 (25.4 against
-  // 28.3 us).  Eight waves like every default shape, so the summation order stays the same.
-  if (bits != 16 && s.mt == 4 && s.nt == 4) {
+  // 32 x 96 tiles against the shape chosen above, for launches that 32 x 96 tiles cover in one or
+  // two rounds of 256 workgroups.  What a workgroup has to pull through its CU's vector-memory
+  // path decides (its rows of the rotated activations plus its weights; with more than two row
+  // tiles 32 x 96 dequantises every weight more often than 64-row tiles, priced at 10 %), and a
+  // change has to promise 10 %.  q/k/v of a 7B attention block in one launch: 192 workgroups of
+  // 64 x 64 but exactly 256 of 32 x 96 (16.3 -> 15.0 us); gate + up of a 7B MLP: 344 against 460
+  // at M = 64 (28.3 -> 25.4 us), 688 of 32 x 32 against 230 at M = 32 (19.7 -> 16.2 us).  Beyond
+  // two rounds the repeated dequantisation costs more than the inflow saves (q/k/v at M = 192:
+  // 47 against 37 us).  Eight waves like every default shape: the summation order stays the same.
+  if (bits != 16 && mtiles >= 2 && s.nt <= 4) {
     auto rounds = [](int wgs) { return (wgs + 255) / 256; };
-    const int wg44 = ((ntiles + 3) / 4) * ((mtiles + 3) / 4);
+    const int wg = ((ntiles + s.nt - 1) / s.nt) * ((mtiles + s.mt - 1) / s.mt);
     const int wg26 = ((ntiles + 5) / 6) * ((mtiles + 1) / 2);
-    const double cost44 = rounds(wg44) * (64 * 2.0 + 64 * wbytes);
-    const double cost26 = rounds(wg26) * (32 * 2.0 + 96 * wbytes) * 1.1;
-    if (rounds(wg44) <= 2 && cost26 < cost44) {
+    const double cost = rounds(wg) * (s.mt * 32.0 + s.nt * 16 * wbytes);
+    const double cost26 = rounds(wg26) * (2 * 32.0 + 6 * 16 * wbytes) * (mtiles > 2 ? 1.1 : 1.0);
+    if (rounds(wg26) <= 2 && cost26 < 0.9 * cost) {
       s.mt = 2;
       s.nt = 6;
     }
