@@ -25,7 +25,6 @@ static int fail(int code, const std::string& msg) {
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-static int padded_tiles(int n) { return ((n + 127) / 128) * 8; }  // 16-channel tiles, whole 128s
 
 // Workspace carve-up for one call with M rows.
 struct WsPlan {
@@ -193,7 +192,6 @@ static int run_main_gemm(const rosaq_packed_t* const* ps, int count, const WsPla
     const rosaq_packed_t* p = ps[i];
     a.seg[i].wS = p->d_wS; a.seg[i].wq = p->d_wq;
     a.seg[i].out = ys[i]; a.seg[i].ldo = ldys[i]; a.seg[i].N = p->c.N;
-    a.seg[i].ntiles = padded_tiles(p->c.N);
   }
   a.M = M;
   a.ks_s = c.K / kKStep; a.G = c.G; a.KS = c.D / kKStep; a.KS_out = 0;
@@ -223,7 +221,6 @@ static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_
   a.nseg = 1;
   a.seg[0].wS = p->d_qf; a.seg[0].wq = nullptr;
   a.seg[0].out = ws + w.xf_b; a.seg[0].ldo = 0; a.seg[0].N = c.D;
-  a.seg[0].ntiles = padded_tiles(c.D);
   a.M = M;
   a.ks_s = c.D / kKStep; a.G = 0; a.KS = c.D / kKStep; a.KS_out = c.D / kKStep;
   a.bits = 4; a.out_frag = 1;

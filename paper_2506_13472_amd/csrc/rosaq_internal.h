@@ -55,7 +55,6 @@ struct GemmSegArgs {
   void* out;             // y (row-major fp16) or xhat fragments
   int64_t ldo;           // leading dimension of y
   int N;                 // valid output channels
-  int ntiles;            // 16-channel tiles in the weight image (multiple of 8)
 };
 struct GemmArgs {
   const void* xf;        // xhat fragments  [mblocks][KS][4][64] x 16 B

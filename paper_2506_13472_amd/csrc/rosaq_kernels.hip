@@ -102,7 +102,6 @@ struct GemmSeg {
   _Float16* out;
   int64_t ldo;
   int N;
-  int ntiles;        // 16-channel tiles in the weight image
   int tile_end;      // exclusive prefix sum of the layers' valid channel tiles, ceil(N / 16)
 };
 // ROSAQ_PROBE_* macros: measurement variants of gemm_kernel (loads only, no weights, no
@@ -826,7 +825,6 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
     d.seg[i].out = static_cast<_Float16*>(sa.out);
     d.seg[i].ldo = sa.ldo;
     d.seg[i].N = sa.N;
-    d.seg[i].ntiles = sa.ntiles;
     d.seg[i].tile_end = tiles;
   }
   d.chunks = (tiles + sh.nt - 1) / sh.nt;
