@@ -735,24 +735,28 @@ GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tu
       if (t < best * 0.999) { best = t; s.mt = mt; s.nt = nt; }
     }
   }
-  // 32 x 96 tiles against the shape chosen above, for launches that 32 x 96 tiles cover in one or
-  // two rounds of 256 workgroups.  What a workgroup has to pull through its CU's vector-memory
-  // path decides (its rows of the rotated activations plus its weights; with more than two row
-  // tiles 32 x 96 dequantises every weight more often than 64-row tiles, priced at 10 %), and a
-  // change has to promise 10 %.  q/k/v of a 7B attention block in one launch: 192 workgroups of
-  // 64 x 64 but exactly 256 of 32 x 96 (16.3 -> 15.0 us); gate + up of a 7B MLP: 344 against 460
-  // at M = 64 (28.3 -> 25.4 us), 688 of 32 x 32 against 230 at M = 32 (19.7 -> 16.2 us).  Beyond
-  // two rounds the repeated dequantisation costs more than the inflow saves (q/k/v at M = 192:
-  // 47 against 37 us).  Eight waves like every default shape: the summation order stays the same.
-  if (bits != 16 && mtiles >= 2 && s.nt <= 4) {
-    auto rounds = [](int wgs) { return (wgs + 255) / 256; };
-    const int wg = ((ntiles + s.nt - 1) / s.nt) * ((mtiles + s.mt - 1) / s.mt);
-    const int wg26 = ((ntiles + 5) / 6) * ((mtiles + 1) / 2);
-    const double cost = rounds(wg) * (s.mt * 32.0 + s.nt * 16 * wbytes);
-    const double cost26 = rounds(wg26) * (2 * 32.0 + 6 * 16 * wbytes) * (mtiles > 2 ? 1.1 : 1.0);
-    if (rounds(wg26) <= 2 && cost26 < 0.9 * cost) {
-      s.mt = 2;
-      s.nt = 6;
+  // 32 x 96 and 64 x 48 tiles against the shape chosen above.  Measured launch times of the
+  // low-bit kernels at 32 to 256 rows order like rounds x (inflow + VALU issue) per workgroup:
+  // the bytes it pulls through its CU's vector-memory path at 128 GB/s (its rows of the rotated
+  // activations plus its weights) plus the four cycles per wave64 VALU instruction of its two
+  // waves per SIMD (9 instructions per 8 weights to convert, 4 per output fragment and group
+  // to scale, 40 per group otherwise).  q/k/v of a 7B attention block in one launch at M = 64:
+  // 192 workgroups of 64 x 64 take 16.2 us, 256 of 32 x 96 15.0, 256 of 64 x 48 14.5; gate + up
+  // of a 7B MLP 28.7 / 26.9 / 26.3 us, at M = 32 32 x 96 tiles make it one round (19.7 -> 16.2).
+  // Eight waves like every default shape: the summation order stays the same.
+  if (bits != 16 && mtiles >= 2) {
+    const double groups = k / 128.0;
+    auto cost = [&](int mt, int nt) {
+      const int wgs = ((ntiles + nt - 1) / nt) * ((mtiles + mt - 1) / mt);
+      const double inflow = (mt * 32.0 + nt * 16 * wbytes) * k / 128e3;
+      const double valu = (nt * ((bits == 3 ? 40 : 36) + 4 * mt) + 40) * (groups / 8) * 8 / 2000.0;
+      return ((wgs + 255) / 256) * (inflow + valu);
+    };
+    double best_alt = cost(s.mt, s.nt) * 0.97;   // a change has to promise 3 %
+    const int mt0 = s.mt, nt0 = s.nt;
+    if (mt0 * nt0 >= 4) {
+      if (cost(2, 6) < best_alt) { best_alt = cost(2, 6); s.mt = 2; s.nt = 6; }
+      if (mtiles >= 3 && cost(4, 3) < best_alt) { best_alt = cost(4, 3); s.mt = 4; s.nt = 3; }
     }
   }
   if (tune.mt == 1 || tune.mt == 2 || tune.mt == 4) s.mt = tune.mt;
