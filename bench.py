@@ -558,8 +558,8 @@ def main():
 
     # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE (x 2.0 by a 256 MiB copy)
     # + WRITE_SIZE (x 1.0), profiles/gemm_kernel_llama7b_attn_M64_int4.md: one 4096 x 4096 launch moves
-    # 13.96 MB + 0.52 MB, a q/k/v launch 33.40 MB + 1.57 MB; the default step averages the two.
-    one, qkv3 = 13636 * 1024 + 512 * 1024, 32622 * 1024 + 1536 * 1024
+    # 13.97 MB + 0.52 MB, a q/k/v launch 33.39 MB + 1.57 MB; the default step averages the two.
+    one, qkv3 = 13640 * 1024 + 512 * 1024, 32612 * 1024 + 1536 * 1024
     traffic = {None: (one + qkv3) // 2, "qkv": qkv3, "o": one}[args.only] if not args.unbatched else one
 
     out = {
