@@ -573,7 +573,9 @@ def main():
                    "launch": "eager" if args.no_graph else "hipGraph per step",
                    "calls": "4 x rosaq_linear_headwise per layer" if args.unbatched else
                             "rosaq_linear_batch(q,k,v) + rosaq_linear_headwise(o) per layer",
-                   "tiles": {k: getattr(args, k) or "heuristic" for k in ("mt", "nt", "wpb", "depth")}},
+                   "tiles": {k: getattr(args, k) or "heuristic" for k in ("mt", "nt", "wpb", "depth")},
+                   "launch_shape_mt_nt_waves_depth": {"one_layer": list(B.rosaq_launch_shape(M, N, D, BITS)),
+                                                       "qkv": list(B.rosaq_launch_shape(M, 3 * N, D, BITS))}},
         "us_per_linear": round(us_call, 3),
         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         "tflops": round(2.0 * M * N * (D + 128) / (us_call * 1e-6) / 1e12, 2),

@@ -199,6 +199,15 @@ int rosaq_stream_probe(const void* src_dev, size_t src_bytes, const void* shared
  *             (2 reuses the rotated activations a previous call left in the workspace) */
 int rosaq_tune(const char* key, int32_t value);
 
+/* Reports, without launching anything (no GPU needed), the workgroup shape the main GEMM of a call
+ * would get: M rows, `channels` output channels in total over the layers of the launch (each layer
+ * rounded up to whole 16-channel tiles by the caller: pass the sum of 16 * ceil(N_i / 16)),
+ * `in_features` = D, `bits` 3 or 4 (16 for an all-fp16 layer), under the current rosaq_tune settings.
+ * shape_out (HOST, 4 ints) receives mt, nt (tiles of 16 rows / 16 channels per workgroup), waves per
+ * workgroup and units in flight per wave.  Errors: ROSAQ_ERR_NULL, ROSAQ_ERR_SHAPE (M, channels < 1,
+ * channels or D not a multiple of 16 / 128), ROSAQ_ERR_ARG (bits). */
+int rosaq_launch_shape(int32_t M, int32_t channels, int32_t in_features, int32_t bits, int32_t* shape_out);
+
 void rosaq_free(rosaq_packed_t* p);
 
 /* Text of the last error on this thread ("" if none). */

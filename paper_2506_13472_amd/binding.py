@@ -22,7 +22,7 @@ LIB_PATH = os.environ.get("ROSAQ_LIB") or os.path.join(os.path.dirname(os.path.a
 
 EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_linear", "rosaq_linear_headwise",
             "rosaq_linear_batch", "rosaq_stream_probe", "rosaq_packed_clone", "rosaq_pca_headwise",
-            "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_free",
+            "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_launch_shape", "rosaq_free",
             "rosaq_last_error"]
 
 
@@ -81,6 +81,8 @@ def lib() -> C.CDLL:
         L.rosaq_packed_export.restype = C.c_int
         L.rosaq_tune.argtypes = [C.c_char_p, i32]
         L.rosaq_tune.restype = C.c_int
+        L.rosaq_launch_shape.argtypes = [i32, i32, i32, i32, C.POINTER(i32)]
+        L.rosaq_launch_shape.restype = C.c_int
         L.rosaq_free.argtypes = [vp]
         L.rosaq_free.restype = None
         L.rosaq_last_error.argtypes = []
@@ -211,6 +213,13 @@ def rosaq_stream_probe(src_ptr: int, src_bytes: int, shared_ptr: int, shared_byt
     _check(lib().rosaq_stream_probe(src_ptr, src_bytes, shared_ptr, shared_bytes,
                                     shared_bytes_per_workgroup, workgroups, threads, sink_ptr,
                                     sink_bytes, stream))
+
+
+def rosaq_launch_shape(M: int, channels: int, in_features: int, bits: int):
+    """(mt, nt, waves per workgroup, units in flight) of the main GEMM such a launch would get."""
+    out = (C.c_int32 * 4)()
+    _check(lib().rosaq_launch_shape(M, channels, in_features, bits, out))
+    return tuple(out)
 
 
 def rosaq_tune(key: str, value: int):

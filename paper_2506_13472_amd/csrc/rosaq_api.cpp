@@ -462,6 +462,16 @@ int rosaq_tune(const char* key, int32_t value) {
   return fail(ROSAQ_ERR_ARG, "unknown tuning key");
 }
 
+int rosaq_launch_shape(int32_t M, int32_t channels, int32_t in_features, int32_t bits, int32_t* shape_out) {
+  if (!shape_out) return fail(ROSAQ_ERR_NULL, "shape_out is NULL");
+  if (M < 1 || channels < 1 || channels % kTileN || in_features < kGroup || in_features % kGroup)
+    return fail(ROSAQ_ERR_SHAPE, "M >= 1, channels a positive multiple of 16, in_features a positive multiple of 128");
+  if (bits != 3 && bits != 4 && bits != 16) return fail(ROSAQ_ERR_ARG, "bits must be 3, 4 or 16");
+  const GemmShape s = pick_gemm_shape(M, channels / kTileN, in_features, bits, g_tune);
+  shape_out[0] = s.mt; shape_out[1] = s.nt; shape_out[2] = s.wpb; shape_out[3] = s.depth;
+  return ROSAQ_OK;
+}
+
 void rosaq_free(rosaq_packed_t* p) {
   if (!p) return;
   if (p->d_blob) (void)hipFree(p->d_blob);

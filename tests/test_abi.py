@@ -194,3 +194,37 @@ def test_pca_headwise_argument_errors():
     assert _code(lambda: B.rosaq_pca_headwise(X, 64, 256, 128)) == -2
     assert _code(lambda: B.rosaq_pca_headwise(X + 1, 64, 256, 256)) == -5
     assert B.lib().rosaq_pca_headwise(X, 64, 256, 256, None, None, None) == -1
+
+
+def test_launch_shape_of_the_named_workloads():
+    """The tile heuristic on the shapes the bench and the design notes quote (host logic only)."""
+    shape = B.rosaq_launch_shape
+    # LLaMA-7B attention at M = 64, INT4: q/k/v in one launch fill the 256 CUs exactly with 64x48 tiles
+    # (3 * 256 channel tiles in chunks of 3), the o projection with 32x32 tiles
+    assert shape(64, 3 * 4096, 4096, 4)[:3] == (4, 3, 8)
+    assert shape(64, 4096, 4096, 4)[:3] == (2, 2, 8)
+    # gate + up of a 7B MLP in one launch: 64x48 at M = 64, 32x96 (one round instead of three) at M = 32
+    assert shape(64, 2 * 11008, 4096, 4)[:3] == (4, 3, 8)
+    assert shape(32, 2 * 11008, 4096, 4)[:3] == (2, 6, 8)
+    # 13B up projection at M = 64: 216 workgroups of 64x64 stay (the alternatives need a second round)
+    assert shape(64, 13824, 5120, 4)[:3] == (4, 4, 8)
+    # prefill-sized calls keep 64x64 tiles
+    assert shape(4096, 4096, 4096, 4)[:3] == (4, 4, 8)
+    assert shape(2048, 13824, 5120, 4)[:3] == (4, 4, 8)
+    # single rows: one 16x16 tile and sixteen waves per workgroup
+    assert shape(1, 4096, 4096, 4) == (1, 1, 16, 1)
+    # all-fp16 layers (the dense rotation) never get the 48- or 96-channel tiles
+    assert shape(64, 4096, 4096, 16)[1] in (1, 2, 4)
+    # overrides go through
+    B.rosaq_tune("mt", 2); B.rosaq_tune("nt", 6)
+    try:
+        assert shape(64, 4096, 4096, 3)[:2] == (2, 6)
+    finally:
+        B.rosaq_tune("mt", 0); B.rosaq_tune("nt", 0)
+    for bad in ((0, 4096, 4096, 4), (64, 4090, 4096, 4), (64, 4096, 4000, 4)):
+        with pytest.raises(B.RosaqError) as e:
+            shape(*bad)
+        assert B.ERR_NAMES[e.value.code] == "SHAPE"
+    with pytest.raises(B.RosaqError) as e:
+        shape(64, 4096, 4096, 5)
+    assert B.ERR_NAMES[e.value.code] == "ARG"
