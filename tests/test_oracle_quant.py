@@ -92,3 +92,25 @@ def test_quantisation_error_bound():
         bound = 0.5 * np.repeat(s.astype(np.float64), 128, axis=1) * (1 + 2 ** -9) + \
             (2 ** bits) * np.repeat(s.astype(np.float64), 128, axis=1) * 2 ** -10
         assert np.all(err <= bound)
+
+
+def test_hand_worked_examples():
+    """tests/golden/quantizer_worked_examples.txt: groups of eight weights quantised by hand from the
+    definition (Sec. 3.3, Eq. 2; asymmetric min-max round-to-nearest)."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "quantizer_worked_examples.txt")
+    cases = 0
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        bits, w, s, z, q = [f.strip() for f in line.split("|")]
+        w = np.array([float(v) for v in w.split()], np.float64)
+        w16 = w.astype(np.float16)[None, :]
+        assert np.array_equal(w16[0].astype(np.float64), w)
+        codes, scales, zeros = O.quantize_groups(w16, int(bits), 8)
+        assert float(scales[0, 0]) == float(s), line
+        assert float(zeros[0, 0]) == float(z), line
+        assert codes[0].tolist() == [int(v) for v in q.split()], line
+        cases += 1
+    assert cases == 6
