@@ -438,7 +438,8 @@ int rosaq_tune(const char* key, int32_t value) {
   if (!std::strncmp(key, "rot_", 4)) {
     const char* k = key + 4;
     if (value < 0 || value > 4 || value == 3) {
-      if (!(std::strcmp(k, "depth") == 0 && value == 3)) return fail(ROSAQ_ERR_ARG, "bad rotation tuning value");
+      if (!((std::strcmp(k, "depth") == 0 || std::strcmp(k, "nt") == 0) && value == 3))
+        return fail(ROSAQ_ERR_ARG, "bad rotation tuning value");
     }
     if (!std::strcmp(k, "mt")) { g_tune_rot.mt = value; return ROSAQ_OK; }
     if (!std::strcmp(k, "nt")) { g_tune_rot.nt = value; return ROSAQ_OK; }
