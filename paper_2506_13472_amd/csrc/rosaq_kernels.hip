@@ -167,6 +167,8 @@ static int map_grid(int chunks, int mgroups) {
 // after the last layer's last one, which loads clamp and stores skip.
 __device__ __forceinline__ void locate_tile(const GemmDev& p, int T, int& si, int& local) {
   si = 0;
+  local = T;
+  if (p.nseg == 1) return;   // the common case stays cheap (uniform branch)
 #pragma unroll
   for (int i = 1; i < kMaxBatch; ++i)
     if (i < p.nseg && T >= p.seg[i - 1].tile_end) si = i;
@@ -177,6 +179,7 @@ __device__ __forceinline__ void locate_tile(const GemmDev& p, int T, int& si, in
 // index would move it to scratch memory).
 __device__ __forceinline__ GemmSeg pick_seg(const GemmDev& p, int si) {
   GemmSeg sg = p.seg[0];
+  if (p.nseg == 1) return sg;
 #pragma unroll
   for (int i = 1; i < kMaxBatch; ++i)
     if (si == i) sg = p.seg[i];
@@ -243,16 +246,26 @@ void gemm_kernel(GemmDev p) {
   // low-bit records of tile nt start at wS_t[nt] and wq_t[nt]
   const uint4* wS_t[NT];
   const uint32_t* wq_t[NT];
+  constexpr int kRecDwordsT = (BITS == 4 ? 256 : 192) + 16;
+  if (p.nseg == 1) {   // one layer: no search, the tiles are consecutive
+    const int valid = (p.seg[0].N + kTileN - 1) / kTileN;
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    constexpr int kRecDwordsT = (BITS == 4 ? 256 : 192) + 16;
-    int si, tile;
-    locate_tile(p, tile0 + nt, si, tile);
-    const GemmSeg sg = pick_seg(p, si);
-    const int valid = (sg.N + kTileN - 1) / kTileN;
-    if (tile >= valid) tile = valid - 1;   // past the end of the list: re-read the last tile
-    wS_t[nt] = sg.wS + static_cast<size_t>(tile) * p.ks_s * 64;
-    wq_t[nt] = sg.wq + static_cast<size_t>(tile) * p.G * kRecDwordsT;
+    for (int nt = 0; nt < NT; ++nt) {
+      const int tile = tile0 + nt < valid ? tile0 + nt : valid - 1;   // past the end: re-read the last tile
+      wS_t[nt] = p.seg[0].wS + static_cast<size_t>(tile) * p.ks_s * 64;
+      wq_t[nt] = p.seg[0].wq + static_cast<size_t>(tile) * p.G * kRecDwordsT;
+    }
+  } else {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      int si, tile;
+      locate_tile(p, tile0 + nt, si, tile);
+      const GemmSeg sg = pick_seg(p, si);
+      const int valid = (sg.N + kTileN - 1) / kTileN;
+      if (tile >= valid) tile = valid - 1;
+      wS_t[nt] = sg.wS + static_cast<size_t>(tile) * p.ks_s * 64;
+      wq_t[nt] = sg.wq + static_cast<size_t>(tile) * p.G * kRecDwordsT;
+    }
   }
 
   floatx4 acc[NT][MT];
