@@ -800,6 +800,12 @@ GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tu
   s.depth = ((s.mt * s.nt <= 4 && s.mt > 1) || s.mt * s.nt == 16) ? 1 : 2;   // skinny tiles: latency, not occupancy
   if (tune.depth >= 1 && tune.depth <= 4) s.depth = tune.depth;
   if (skinny16) s.depth = 1;
+  // two tiles per workgroup at a single row tile, in a launch that does not fill one round of
+  // 256 workgroups: sixteen waves with two units in flight (13824 -> 5120 at M = 1: 160
+  // workgroups, 13.5 against 14.9 us with eight waves; launches of several rounds lose 15-25 %)
+  const bool skinny16x2 = tune.wpb == 0 && tune.depth == 0 && bits != 16 && s.mt == 1 && s.nt == 2 &&
+                          (ntiles + 1) / 2 * mtiles <= 256;
+  if (skinny16x2) { s.wpb = 16; s.depth = 2; }
   // deepest prefetch that still fits the register file without spilling
   int max_depth = 4;
   if (s.wpb == 4) {

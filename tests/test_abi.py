@@ -213,6 +213,10 @@ def test_launch_shape_of_the_named_workloads():
     assert shape(2048, 13824, 5120, 4)[:3] == (4, 4, 8)
     # single rows: one 16x16 tile and sixteen waves per workgroup
     assert shape(1, 4096, 4096, 4) == (1, 1, 16, 1)
+    # two tiles per workgroup in a launch of less than one round (13B down projection): sixteen waves too;
+    # launches of several rounds keep eight
+    assert shape(1, 5120, 13824, 4) == (1, 2, 16, 2)
+    assert shape(1, 13824, 5120, 4) == (1, 2, 8, 2)
     # all-fp16 layers (the dense rotation) never get the 48- or 96-channel tiles
     assert shape(64, 4096, 4096, 16)[1] in (1, 2, 4)
     # overrides go through
