@@ -485,3 +485,23 @@ def test_seeded_random_batches_and_tiles():
             check_output(yh[:, :N], x, Q, ref)
         for p in ps:
             p.free()
+
+
+@pytest.mark.parametrize("rot_mt", [2, 4])
+def test_dense_rotation_with_48_channel_tiles(rot_mt):
+    """The all-fp16 rotation launch with 48-channel tiles on a width they do not divide (40 channel
+    tiles): the last chunk runs past the end and the rotated activations still come out right."""
+    print(f"case dense rotation rot_mt={rot_mt} rot_nt=3", flush=True)
+    lay, Q, lam = make_case(61, 50, 640, 200, 300, O.MODE_FULL)
+    ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_FULL)
+    p = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_FULL)
+    y_default = run_gpu(p, lay["x"])
+    B.rosaq_tune("rot_mt", rot_mt); B.rosaq_tune("rot_nt", 3)
+    try:
+        y = run_gpu(p, lay["x"])
+    finally:
+        B.rosaq_tune("rot_mt", 0); B.rosaq_tune("rot_nt", 0)
+    check_output(y, lay["x"], Q, ref)
+    # same eight-wave summation order as the default rotation tiles: identical rotated activations
+    assert np.array_equal(y.view(np.uint16), y_default.view(np.uint16))
+    p.free()
