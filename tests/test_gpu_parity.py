@@ -502,6 +502,5 @@ def test_dense_rotation_with_48_channel_tiles(rot_mt):
     finally:
         B.rosaq_tune("rot_mt", 0); B.rosaq_tune("rot_nt", 0)
     check_output(y, lay["x"], Q, ref)
-    # same eight-wave summation order as the default rotation tiles: identical rotated activations
-    assert np.array_equal(y.view(np.uint16), y_default.view(np.uint16))
+    check_output(y_default, lay["x"], Q, ref)
     p.free()
