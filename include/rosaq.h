@@ -208,6 +208,14 @@ int rosaq_tune(const char* key, int32_t value);
  * channels or D not a multiple of 16 / 128), ROSAQ_ERR_ARG (bits). */
 int rosaq_launch_shape(int32_t M, int32_t channels, int32_t in_features, int32_t bits, int32_t* shape_out);
 
+/* Testing aid, host only: the main GEMM's map from workgroup index to (channel chunk, row group) for a
+ * launch of `chunks` x `row_groups` tiles (workgroup % 8 is the XCD; inside an XCD consecutive workgroups
+ * form blocks of 8 chunks x 4 row groups).  workgroup < 0: returns the grid size (>= chunks * row_groups;
+ * the surplus are padding workgroups that exit at once).  Otherwise returns 1 and the pair, or 0 (and -1,
+ * -1) for a padding workgroup.  Errors (negative): ROSAQ_ERR_SHAPE, ROSAQ_ERR_NULL. */
+int rosaq_block_map(int32_t workgroup, int32_t chunks, int32_t row_groups, int32_t* chunk_out,
+                    int32_t* row_group_out);
+
 void rosaq_free(rosaq_packed_t* p);
 
 /* Text of the last error on this thread ("" if none). */

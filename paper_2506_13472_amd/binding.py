@@ -22,7 +22,7 @@ LIB_PATH = os.environ.get("ROSAQ_LIB") or os.path.join(os.path.dirname(os.path.a
 
 EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_linear", "rosaq_linear_headwise",
             "rosaq_linear_batch", "rosaq_stream_probe", "rosaq_packed_clone", "rosaq_pca_headwise",
-            "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_launch_shape", "rosaq_free",
+            "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_launch_shape", "rosaq_block_map", "rosaq_free",
             "rosaq_last_error"]
 
 
@@ -83,6 +83,8 @@ def lib() -> C.CDLL:
         L.rosaq_tune.restype = C.c_int
         L.rosaq_launch_shape.argtypes = [i32, i32, i32, i32, C.POINTER(i32)]
         L.rosaq_launch_shape.restype = C.c_int
+        L.rosaq_block_map.argtypes = [i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
+        L.rosaq_block_map.restype = C.c_int
         L.rosaq_free.argtypes = [vp]
         L.rosaq_free.restype = None
         L.rosaq_last_error.argtypes = []
@@ -220,6 +222,17 @@ def rosaq_launch_shape(M: int, channels: int, in_features: int, bits: int):
     out = (C.c_int32 * 4)()
     _check(lib().rosaq_launch_shape(M, channels, in_features, bits, out))
     return tuple(out)
+
+
+def rosaq_block_map(workgroup: int, chunks: int, row_groups: int):
+    """Grid size for workgroup < 0; else (chunk, row_group), or None for a padding workgroup."""
+    c, m = C.c_int32(-1), C.c_int32(-1)
+    r = lib().rosaq_block_map(workgroup, chunks, row_groups, C.byref(c), C.byref(m))
+    if r < 0:
+        _check(r)
+    if workgroup < 0:
+        return r
+    return (c.value, m.value) if r else None
 
 
 def rosaq_tune(key: str, value: int):

@@ -473,6 +473,17 @@ int rosaq_launch_shape(int32_t M, int32_t channels, int32_t in_features, int32_t
   return ROSAQ_OK;
 }
 
+int rosaq_block_map(int32_t workgroup, int32_t chunks, int32_t row_groups, int32_t* chunk_out, int32_t* row_group_out) {
+  if (chunks < 1 || row_groups < 1) return fail(ROSAQ_ERR_SHAPE, "chunks and row_groups must be positive");
+  if (workgroup >= 0 && (!chunk_out || !row_group_out)) return fail(ROSAQ_ERR_NULL, "output pointer is NULL");
+  int c = -1, m = -1;
+  const int r = block_map_host(workgroup, chunks, row_groups, &c, &m);
+  if (workgroup < 0) return r;
+  *chunk_out = r ? c : -1;
+  *row_group_out = r ? m : -1;
+  return r;
+}
+
 void rosaq_free(rosaq_packed_t* p) {
   if (!p) return;
   if (p->d_blob) (void)hipFree(p->d_blob);

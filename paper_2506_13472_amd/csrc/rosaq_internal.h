@@ -74,6 +74,9 @@ struct GemmTune { int mt = 0, nt = 0, wpb = 0, depth = 0; };   // 0 = heuristic
 struct GemmShape { int mt, nt, wpb, depth; };
 GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tune);
 int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream);
+// Host copy of the kernel's workgroup -> (channel chunk, row group) map: b < 0 returns the grid
+// size, otherwise 1 and the pair, or 0 for a padding workgroup that exits at once.
+int block_map_host(int b, int chunks, int mgroups, int* chunk, int* mg);
 int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_dev,
                   void* xf, void* stream);
 int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void* qh,

@@ -136,7 +136,7 @@ struct GemmDev {
 // chunk and every row group (which at large M streams the whole activation matrix through
 // every L2 once per chunk).  For up to 4 row groups this is the plain order: chunk-major.
 constexpr int kMapCols = 8, kMapRows = 4;
-__device__ __forceinline__ bool map_block(int b, int chunks, int mgroups, int& chunk, int& mg) {
+__host__ __device__ __forceinline__ bool map_block(int b, int chunks, int mgroups, int& chunk, int& mg) {
   const int xcd = b & 7, local = b >> 3;
   if (mgroups <= kMapRows) {                              // plain chunk-major order
     mg = local % mgroups;
@@ -145,9 +145,10 @@ __device__ __forceinline__ bool map_block(int b, int chunks, int mgroups, int& c
   }
   const int tr = kMapRows;
   const int cx = (chunks + 7) >> 3;                       // chunk slots of one XCD
-  const int nbc = (cx + kMapCols - 1) / kMapCols;
-  const int block = local / (kMapCols * tr), inner = local - block * (kMapCols * tr);
-  const int ci = (block % nbc) * kMapCols + inner / tr;
+  const int cols = cx < kMapCols ? cx : kMapCols;         // narrow launches: narrower blocks, less padding
+  const int nbc = (cx + cols - 1) / cols;
+  const int block = local / (cols * tr), inner = local - block * (cols * tr);
+  const int ci = (block % nbc) * cols + inner / tr;
   mg = (block / nbc) * tr + inner % tr;
   chunk = xcd + 8 * ci;
   return ci < cx && chunk < chunks && mg < mgroups;
@@ -156,8 +157,13 @@ static int map_grid(int chunks, int mgroups) {
   if (mgroups <= kMapRows) return ((chunks + 7) / 8) * 8 * mgroups;
   const int tr = kMapRows;
   const int cx = (chunks + 7) / 8;
-  const int nbc = (cx + kMapCols - 1) / kMapCols;
-  return 8 * nbc * ((mgroups + tr - 1) / tr) * kMapCols * tr;
+  const int cols = cx < kMapCols ? cx : kMapCols;
+  const int nbc = (cx + cols - 1) / cols;
+  return 8 * nbc * ((mgroups + tr - 1) / tr) * cols * tr;
+}
+int block_map_host(int b, int chunks, int mgroups, int* chunk, int* mg) {
+  if (b < 0) return map_grid(chunks, mgroups);          // the grid size
+  return map_block(b, chunks, mgroups, *chunk, *mg) ? 1 : 0;
 }
 
 // The layers of a launch are one list of channel tiles (layer 0's valid tiles, then layer 1's,

@@ -232,3 +232,31 @@ def test_launch_shape_of_the_named_workloads():
     with pytest.raises(B.RosaqError) as e:
         shape(64, 4096, 4096, 5)
     assert B.ERR_NAMES[e.value.code] == "ARG"
+
+
+def test_block_map_covers_every_tile_exactly_once():
+    """The workgroup -> (channel chunk, row group) map of the main GEMM: a bijection onto the launch's tiles
+    plus padding workgroups, with every chunk on the XCD (workgroup % 8) equal to chunk % 8, for all small
+    launch shapes and the ones of the named workloads."""
+    shapes = [(c, m) for c in range(1, 70) for m in range(1, 14)]
+    shapes += [(256, 1), (128, 2), (192, 1), (230, 2), (459, 1), (216, 64), (64, 64), (80, 16), (500, 64), (257, 9)]
+    for chunks, mgroups in shapes:
+        grid = B.rosaq_block_map(-1, chunks, mgroups)
+        assert grid >= chunks * mgroups and grid % 8 == 0
+        seen = set()
+        for b in range(grid):
+            t = B.rosaq_block_map(b, chunks, mgroups)
+            if t is None:
+                continue
+            c, m = t
+            assert 0 <= c < chunks and 0 <= m < mgroups
+            assert c % 8 == b % 8                      # a chunk's workgroups share one XCD's L2
+            assert t not in seen
+            seen.add(t)
+        assert len(seen) == chunks * mgroups, (chunks, mgroups)
+        # padding stays bounded: chunk slots round up to whole XCD columns (and to blocks of 8 from 8 on),
+        # row groups to blocks of 4
+        cx = (chunks + 7) // 8
+        assert grid <= 8 * (cx + (7 if cx >= 8 else 0)) * (mgroups + 3)
+    with pytest.raises(B.RosaqError):
+        B.rosaq_block_map(0, 0, 1)
