@@ -208,6 +208,15 @@ int rosaq_tune(const char* key, int32_t value);
  * channels or D not a multiple of 16 / 128), ROSAQ_ERR_ARG (bits). */
 int rosaq_launch_shape(int32_t M, int32_t channels, int32_t in_features, int32_t bits, int32_t* shape_out);
 
+/* Testing aid, host only: the weight image exactly as the kernels read it, rebuilt from the handle's
+ * canonical arrays.  which = 0: fp16 salient fragments [tiles][K/32][64 lanes][8 halves]; which = 1:
+ * low-bit records [tiles][G] of 1088 bytes (INT4: [64 lanes][4 dwords] codes, then 16 dwords
+ * scale | zero << 16) or 832 bytes (INT3: [64 lanes][3 dwords]); tiles = 8 * ceil(N / 128).
+ * Lane l of tile t holds output channel 16 t + l % 16 and, per 32-channel k-step, the 8 storage-order
+ * channels 8 (l / 16) .. + 7.  out_host may be NULL to query the size; *bytes is capacity in, size out.
+ * Errors: ROSAQ_ERR_NULL, ROSAQ_ERR_ARG, ROSAQ_ERR_WORKSPACE (buffer too small; *bytes set to the need). */
+int rosaq_packed_image(const rosaq_packed_t* p, int32_t which, void* out_host, size_t* bytes);
+
 /* Testing aid, host only: the main GEMM's map from workgroup index to (channel chunk, row group) for a
  * launch of `chunks` x `row_groups` tiles (workgroup % 8 is the XCD; inside an XCD consecutive workgroups
  * form blocks of 8 chunks x 4 row groups).  workgroup < 0: returns the grid size (>= chunks * row_groups;

@@ -22,7 +22,7 @@ LIB_PATH = os.environ.get("ROSAQ_LIB") or os.path.join(os.path.dirname(os.path.a
 
 EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_linear", "rosaq_linear_headwise",
             "rosaq_linear_batch", "rosaq_stream_probe", "rosaq_packed_clone", "rosaq_pca_headwise",
-            "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_launch_shape", "rosaq_block_map", "rosaq_free",
+            "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_launch_shape", "rosaq_block_map", "rosaq_packed_image", "rosaq_free",
             "rosaq_last_error"]
 
 
@@ -83,6 +83,8 @@ def lib() -> C.CDLL:
         L.rosaq_tune.restype = C.c_int
         L.rosaq_launch_shape.argtypes = [i32, i32, i32, i32, C.POINTER(i32)]
         L.rosaq_launch_shape.restype = C.c_int
+        L.rosaq_packed_image.argtypes = [vp, i32, vp, C.POINTER(sz)]
+        L.rosaq_packed_image.restype = C.c_int
         L.rosaq_block_map.argtypes = [i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
         L.rosaq_block_map.restype = C.c_int
         L.rosaq_free.argtypes = [vp]
@@ -222,6 +224,15 @@ def rosaq_launch_shape(M: int, channels: int, in_features: int, bits: int):
     out = (C.c_int32 * 4)()
     _check(lib().rosaq_launch_shape(M, channels, in_features, bits, out))
     return tuple(out)
+
+
+def rosaq_packed_image(p: "Packed", which: int) -> np.ndarray:
+    """The weight image the kernels read (0: fp16 fragments, 1: low-bit records) as uint32 words."""
+    n = C.c_size_t(0)
+    _check(lib().rosaq_packed_image(p.handle, which, None, C.byref(n)))
+    out = np.empty(n.value // 4, np.uint32)
+    _check(lib().rosaq_packed_image(p.handle, which, out.ctypes.data_as(C.c_void_p), C.byref(n)))
+    return out
 
 
 def rosaq_block_map(workgroup: int, chunks: int, row_groups: int):

@@ -473,6 +473,21 @@ int rosaq_launch_shape(int32_t M, int32_t channels, int32_t in_features, int32_t
   return ROSAQ_OK;
 }
 
+int rosaq_packed_image(const rosaq_packed_t* p, int32_t which, void* out_host, size_t* bytes) {
+  if (!p || !bytes) return fail(ROSAQ_ERR_NULL, "handle or bytes is NULL");
+  if (which != 0 && which != 1) return fail(ROSAQ_ERR_ARG, "which must be 0 (fp16 fragments) or 1 (low-bit records)");
+  DeviceImage img;
+  build_device_image(p->c, nullptr, &img);
+  const std::vector<uint32_t>& v = which == 0 ? img.wS : img.wq;
+  const size_t need = v.size() * sizeof(uint32_t);
+  if (out_host) {
+    if (*bytes < need) { *bytes = need; return fail(ROSAQ_ERR_WORKSPACE, "image buffer too small"); }
+    if (need) std::memcpy(out_host, v.data(), need);
+  }
+  *bytes = need;
+  return ROSAQ_OK;
+}
+
 int rosaq_block_map(int32_t workgroup, int32_t chunks, int32_t row_groups, int32_t* chunk_out, int32_t* row_group_out) {
   if (chunks < 1 || row_groups < 1) return fail(ROSAQ_ERR_SHAPE, "chunks and row_groups must be positive");
   if (workgroup >= 0 && (!chunk_out || !row_group_out)) return fail(ROSAQ_ERR_NULL, "output pointer is NULL");

@@ -362,8 +362,9 @@ void build_device_image(const Canonical& c, const float* Q, DeviceImage* img) {
     std::vector<uint32_t>().swap(img->sz);
   }
 
-  // fp16 rotation fragments
+  // fp16 rotation fragments (skipped when the caller has no Q at hand and only wants the weights)
   img->qf.clear();
+  if (Q == nullptr) return;
   if (c.q_mode == ROSAQ_Q_FULL) {
     // rotation as a linear layer with "weight" Q^T, output columns already in
     // storage order: fragment row p is rotated channel perm[p].

@@ -133,3 +133,74 @@ def test_rotation_absorbed_packs_the_same_arrays():
                              rotation_absorbed=True)
     _compare(p, ref)
     assert p.q_mode == B.Q_NONE
+
+
+def _decode_image(wS_words, wq_words, N, D, K, bits):
+    """The documented fragment layout read back with plain loops, written from the layout's description
+    and not from the packer: returns W_S bits [N x K], codes [N x (D-K)], scale bits and zero bits [N x G]."""
+    G = (D - K) // 128
+    tiles = 8 * ((N + 127) // 128)
+    ks_s = K // 32
+    W_S = np.zeros((N, K), np.uint16)
+    halves = wS_words.view(np.uint16).reshape(tiles, max(ks_s, 1), 64, 8) if ks_s else None
+    for n in range(N):
+        t, r = divmod(n, 16)
+        for ks in range(ks_s):
+            for j in range(4):                       # lane = 16 j + r holds channels 32 ks + 8 j .. + 7
+                W_S[n, 32 * ks + 8 * j: 32 * ks + 8 * j + 8] = halves[t, ks, 16 * j + r]
+    code_dwords = 256 if bits == 4 else 192
+    rec = wq_words.reshape(tiles, max(G, 1), code_dwords + 16) if G else None
+    codes = np.zeros((N, D - K), np.uint8)
+    scales = np.zeros((N, G), np.uint16)
+    zeros = np.zeros((N, G), np.uint16)
+    for n in range(N):
+        t, r = divmod(n, 16)
+        for g in range(G):
+            sz = int(rec[t, g, code_dwords + r])
+            scales[n, g], zeros[n, g] = sz & 0xFFFF, sz >> 16
+            for j in range(4):
+                lane = 16 * j + r
+                if bits == 4:
+                    w = [int(v) for v in rec[t, g, 4 * lane: 4 * lane + 4]]
+                    for ks in range(4):
+                        for e in range(8):           # element e of k-step ks: nibble (e >> 1) + 4 (e & 1)
+                            codes[n, 128 * g + 32 * ks + 8 * j + e] = (w[ks] >> (4 * ((e >> 1) + 4 * (e & 1)))) & 15
+                else:
+                    w = [int(v) for v in rec[t, g, 3 * lane: 3 * lane + 3]]
+                    for ks in range(4):
+                        for e in range(8):           # pair P = 4 ks + e / 2; odd elements in the high half
+                            P, half = 4 * ks + (e >> 1), 16 * (e & 1)
+                            if P < 15:
+                                c = (w[P // 5] >> (half + 3 * (P % 5))) & 7
+                            else:                    # the sixteenth pair: bit b of the code in dword b, bit 15 / 31
+                                c = sum(((w[b] >> (half + 15)) & 1) << b for b in range(3))
+                            codes[n, 128 * g + 32 * ks + 8 * j + e] = c
+    return W_S, codes, scales, zeros
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,D,K", [(40, 384, 128), (130, 256, 0), (17, 256, 256)])
+def test_device_image_follows_the_documented_fragment_layout(bits, N, D, K):
+    """rosaq_packed_image (what the kernels read) decoded by an independent reader of the layout gives back
+    the canonical arrays; rows beyond N are padding (zero weights, scale 2^-14)."""
+    lay = synth.make_layer(900 + bits + N, 4, D, N, 64)
+    lam = np.abs(lay["X_cal"]).mean(axis=0)
+    p = B.rosaq_pack_weights(lay["W"], None, lam, K, bits, B.Q_NONE, host_only=True)
+    got = B.rosaq_packed_export(p)
+    wS = B.rosaq_packed_image(p, 0)
+    wq = B.rosaq_packed_image(p, 1)
+    tiles = 8 * ((N + 127) // 128)
+    G = (D - K) // 128
+    assert wS.size == tiles * (K // 32) * 64 * 4
+    assert wq.size == tiles * G * ((256 if bits == 4 else 192) + 16)
+    W_S, codes, scales, zeros = _decode_image(wS, wq, N, D, K, bits)
+    assert np.array_equal(W_S, got["W_S"].view(np.uint16).reshape(N, K))
+    assert np.array_equal(codes, got["codes"].reshape(N, D - K))
+    assert np.array_equal(scales, got["scales"].view(np.uint16).reshape(N, G))
+    assert np.array_equal(zeros, got["zeros"].view(np.uint16).reshape(N, G))
+    if G:
+        rec = wq.reshape(tiles, G, -1)
+        pad_rows = [(n // 16, n % 16) for n in range(N, tiles * 16)]
+        cd = 256 if bits == 4 else 192
+        assert all(int(rec[t, g, cd + r]) == 0x0400 for t, r in pad_rows for g in range(G))
+    p.free()
