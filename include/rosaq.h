@@ -36,6 +36,7 @@ extern "C" {
 #define ROSAQ_ERR_HIP       (-8)  /* a HIP call failed (text in rosaq_last_error)                */
 #define ROSAQ_ERR_NOMEM     (-9)  /* host allocation failed                                      */
 #define ROSAQ_ERR_HOSTONLY  (-10) /* handle was packed with host_only and has no device buffers  */
+#define ROSAQ_ERR_NOCONVERGE (-11) /* the Jacobi eigensolver did not reach its tolerance          */
 
 /* Rotation kinds.  NONE is R = I (the rotation-less "Mixed" baseline, Sec. 4.1);
  * FULL is the layer-wise PCA rotation (Sec. 3.1, Eq. 4); HEADWISE is the block
@@ -49,8 +50,10 @@ extern "C" {
  * 128-channel head, the setting the weight-splitting appendix uses for the attention
  * output projection (32 per head).  The other three are the ablation rules of the
  * salient-channel appendix: BOTTOM = the K smallest eigenvalues; CONSECUTIVE = channels
- * select_arg .. select_arg+K-1 (the caller draws the random start); TOP_AND_BOTTOM =
- * K/2 largest plus K/2 smallest among the rest (total K, so the format is unchanged). */
+ * select_arg .. select_arg+K-1 (the caller draws the random start); TOP_AND_BOTTOM = the
+ * channels of TOP and of BOTTOM together: K/2 largest plus K/2 smallest among the rest.  K is
+ * always the size of the FP16 block, so the appendix's combined scheme for its K' (K' from Top
+ * and K' from Bottom) is this rule with K = 2 K'. */
 #define ROSAQ_SELECT_TOP            0
 #define ROSAQ_SELECT_TOP_PER_HEAD   1
 #define ROSAQ_SELECT_BOTTOM         2
@@ -108,8 +111,19 @@ int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_pack
  * Errors: NULL, NOMEM, HIP. */
 int rosaq_packed_clone(const rosaq_packed_t* src, void* hip_stream, rosaq_packed_t** out);
 
-/* Bytes of DEVICE workspace rosaq_linear* needs for M rows (0 on a bad handle). */
+/* Bytes of DEVICE workspace to give rosaq_linear* for M rows (0 on a bad handle): the rotated
+ * activations, a few KiB of tickets, and (calls of up to 64 rows) room for the fp32 partial output
+ * tiles of a launch whose contraction is split over up to 16 workgroups per tile.  A call accepts a
+ * smaller workspace as long as the first two parts fit (it then splits less, or not at all, and
+ * runs slower); it fails with ROSAQ_ERR_WORKSPACE below that. */
 size_t rosaq_workspace_bytes(const rosaq_packed_t* p, int32_t M);
+
+/* The smallest workspace a call with M rows accepts (no room for split launches). */
+size_t rosaq_workspace_bytes_min(const rosaq_packed_t* p, int32_t M);
+
+/* rosaq_workspace_bytes for one rosaq_linear_batch call over these `count` layers (their output
+ * widths add up). */
+size_t rosaq_workspace_bytes_batch(const rosaq_packed_t* const* layers, int32_t count, int32_t M);
 
 /* rosaq_linear - Eq. 3 for q_mode NONE or FULL:
  *     xhat = x fp16(Q)            (FULL; fp32 accumulate, xhat rounded to fp16)
@@ -170,7 +184,7 @@ int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t*
  *   eigenvalues_host  HOST fp64 [D], descending inside every head, negative round-off clamped to 0
  *   X_dev             DEVICE fp16 [n_cal x D] calibration activations, row r at X + r*ldx
  * Allocates its own device scratch and waits for the result (calibration time, not the hot path).
- * Errors: NULL, SHAPE, ALIGN, HIP, NONFINITE (no convergence within 60 sweeps). */
+ * Errors: NULL, SHAPE, ALIGN, HIP, NOCONVERGE (tolerance not reached within 60 sweeps). */
 int rosaq_pca_headwise(const void* X_dev, int32_t n_cal, int32_t D, int64_t ldx, float* Q_host,
                        double* eigenvalues_host, void* hip_stream);
 
@@ -195,16 +209,22 @@ int rosaq_stream_probe(const void* src_dev, size_t src_bytes, const void* shared
  *             would not fit the register file fall back to 8)
  *   "depth"   units (a group, or four fp16 k-steps) a wave keeps in flight (0 = default, 1-4; clamped to
  *             what the chosen tile fits without spilling)
+ *   "splits", "rot_splits"  workgroups sharing one output tile, each over its own part of the
+ *             contraction (0 = heuristic, 1 = never split, 2-16; calls of up to 64 rows only)
  *   "stages"  3 = whole call (default), 1 = prologue kernels only, 2 = main GEMM only
- *             (2 reuses the rotated activations a previous call left in the workspace) */
+ *             (2 reuses the rotated activations a previous call left in the workspace)
+ * For benchmarks and tests only: the settings are process-wide and not synchronised, so no other
+ * thread may be inside a rosaq_linear* call while they change, and "stages" other than 3 makes
+ * every later call skip part of its work while still returning ROSAQ_OK. */
 int rosaq_tune(const char* key, int32_t value);
 
 /* Reports, without launching anything (no GPU needed), the workgroup shape the main GEMM of a call
  * would get: M rows, `channels` output channels in total over the layers of the launch (each layer
  * rounded up to whole 16-channel tiles by the caller: pass the sum of 16 * ceil(N_i / 16)),
  * `in_features` = D, `bits` 3 or 4 (16 for an all-fp16 layer), under the current rosaq_tune settings.
- * shape_out (HOST, 4 ints) receives mt, nt (tiles of 16 rows / 16 channels per workgroup), waves per
- * workgroup and units in flight per wave.  Errors: ROSAQ_ERR_NULL, ROSAQ_ERR_SHAPE (M, channels < 1,
+ * shape_out (HOST, 5 ints) receives mt, nt (tiles of 16 rows / 16 channels per workgroup), waves per
+ * workgroup, units in flight per wave and the number of workgroups that split one tile's contraction
+ * (given a workspace of rosaq_workspace_bytes_batch size).  Errors: ROSAQ_ERR_NULL, ROSAQ_ERR_SHAPE (M, channels < 1,
  * channels or D not a multiple of 16 / 128), ROSAQ_ERR_ARG (bits). */
 int rosaq_launch_shape(int32_t M, int32_t channels, int32_t in_features, int32_t bits, int32_t* shape_out);
 

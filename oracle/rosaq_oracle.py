@@ -232,7 +232,7 @@ RULE_TOP = 0            # Sec. 3.2: the K largest eigenvalues (the method)
 RULE_TOP_PER_HEAD = 1   # weight-splitting appendix: the same number of salient channels in every head
 RULE_BOTTOM = 2         # ablation of App. B: the K smallest eigenvalues
 RULE_CONSECUTIVE = 3    # ablation of App. B: K consecutive channels from a given start ("Random")
-RULE_TOP_AND_BOTTOM = 4 # ablation of App. B: K/2 largest and K/2 smallest
+RULE_TOP_AND_BOTTOM = 4 # ablation of App. B: the channels of Top and of Bottom together (K counts both halves)
 
 
 def select_salient(lam, K: int, rule: int = RULE_TOP, arg: int = 0, head_dim: int = 128):
@@ -244,8 +244,12 @@ def select_salient(lam, K: int, rule: int = RULE_TOP, arg: int = 0, head_dim: in
                    32 per head for the attention output projection)
     BOTTOM         the K smallest eigenvalues
     CONSECUTIVE    channels arg .. arg + K - 1 (the caller draws the random start)
-    TOP_AND_BOTTOM K/2 largest, then K/2 smallest among the remaining channels
-                   (reading of "takes both": the total stays K so the storage format is unchanged)
+    TOP_AND_BOTTOM the union of what TOP and BOTTOM pick with K/2 each: the K/2 largest, then
+                   the K/2 smallest among the remaining channels.  K is the size of the fp16
+                   block, as for every rule, so the appendix's combined scheme for its K' (both
+                   the K' channels of Top and the K' channels of Bottom) is this rule with
+                   K = 2 K'.  "Among the remaining" only matters when eigenvalues tie across
+                   the two halves or K > D/2; it keeps the two halves disjoint.
     """
     lam = as_f64(lam)
     D = lam.shape[0]

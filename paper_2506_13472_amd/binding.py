@@ -16,11 +16,12 @@ Q_NONE, Q_FULL, Q_HEADWISE = 0, 1, 2
 SELECT_TOP, SELECT_TOP_PER_HEAD, SELECT_BOTTOM, SELECT_CONSECUTIVE, SELECT_TOP_AND_BOTTOM = range(5)
 
 ERR_NAMES = {0: "OK", -1: "NULL", -2: "SHAPE", -3: "ARG", -4: "MODE", -5: "ALIGN",
-             -6: "WORKSPACE", -7: "NONFINITE", -8: "HIP", -9: "NOMEM", -10: "HOSTONLY"}
+             -6: "WORKSPACE", -7: "NONFINITE", -8: "HIP", -9: "NOMEM", -10: "HOSTONLY",
+             -11: "NOCONVERGE"}
 
 LIB_PATH = os.environ.get("ROSAQ_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "librosaq.so")
 
-EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_linear", "rosaq_linear_headwise",
+EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_workspace_bytes_batch", "rosaq_workspace_bytes_min", "rosaq_linear", "rosaq_linear_headwise",
             "rosaq_linear_batch", "rosaq_stream_probe", "rosaq_packed_clone", "rosaq_pca_headwise",
             "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_launch_shape", "rosaq_block_map", "rosaq_packed_image", "rosaq_free",
             "rosaq_last_error"]
@@ -65,6 +66,10 @@ def lib() -> C.CDLL:
         L.rosaq_packed_clone.restype = C.c_int
         L.rosaq_workspace_bytes.argtypes = [vp, i32]
         L.rosaq_workspace_bytes.restype = sz
+        L.rosaq_workspace_bytes_min.argtypes = [vp, i32]
+        L.rosaq_workspace_bytes_min.restype = sz
+        L.rosaq_workspace_bytes_batch.argtypes = [C.POINTER(vp), i32, i32]
+        L.rosaq_workspace_bytes_batch.restype = sz
         for f in (L.rosaq_linear, L.rosaq_linear_headwise):
             f.argtypes = [vp, vp, i32, i64, vp, i64, vp, sz, vp]
             f.restype = C.c_int
@@ -175,6 +180,15 @@ def rosaq_workspace_bytes(p: Packed, M: int) -> int:
     return lib().rosaq_workspace_bytes(p.handle, M)
 
 
+def rosaq_workspace_bytes_min(p: Packed, M: int) -> int:
+    return lib().rosaq_workspace_bytes_min(p.handle, M)
+
+
+def rosaq_workspace_bytes_batch(layers, M: int) -> int:
+    arr = (C.c_void_p * len(layers))(*[p.handle.value for p in layers])
+    return lib().rosaq_workspace_bytes_batch(arr, len(layers), M)
+
+
 def rosaq_linear(p: Packed, x_ptr: int, M: int, ldx: int, y_ptr: int, ldy: int, ws_ptr: int,
                  ws_bytes: int, stream: int = 0):
     _check(lib().rosaq_linear(p.handle, x_ptr, M, ldx, y_ptr, ldy, ws_ptr, ws_bytes, stream))
@@ -220,8 +234,8 @@ def rosaq_stream_probe(src_ptr: int, src_bytes: int, shared_ptr: int, shared_byt
 
 
 def rosaq_launch_shape(M: int, channels: int, in_features: int, bits: int):
-    """(mt, nt, waves per workgroup, units in flight) of the main GEMM such a launch would get."""
-    out = (C.c_int32 * 4)()
+    """(mt, nt, waves per workgroup, units in flight, splits) of the main GEMM such a launch would get."""
+    out = (C.c_int32 * 5)()
     _check(lib().rosaq_launch_shape(M, channels, in_features, bits, out))
     return tuple(out)
 

@@ -2,8 +2,10 @@
 // the per-call launch sequence.  No arithmetic of the method happens here.
 #include <hip/hip_runtime_api.h>
 
+#include <climits>
 #include <cstdlib>
 #include <cstring>
+#include <exception>
 #include <new>
 #include <type_traits>
 
@@ -27,11 +29,22 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 
 // Workspace carve-up for one call with M rows.
+// [xhat fragments | second copy for the dense rotation | tickets of the rotation GEMM and of the
+// main GEMM | fp32 partial tiles of split launches].  `required` is what a call cannot do without;
+// whatever the caller gives beyond it is room for partial tiles.
 struct WsPlan {
-  size_t xf_a = 0, xf_b = 0, total = 0;
+  size_t xf_a = 0, xf_b = 0, tickets = 0, part = 0, required = 0, total = 0;
 };
+constexpr size_t kTicketBytes = 2 * static_cast<size_t>(kTicketsPerLaunch) * sizeof(uint32_t);
 
-static WsPlan plan_workspace(const rosaq_packed& p, int M) {
+// partial tiles of one launch at the largest split: rows padded to whole tiles, fp32
+static size_t part_room(int M, size_t channels) {
+  if (M > 64) return 0;                                   // only launches of up to 64 rows are split
+  const size_t rows = M > 32 ? 64 : (M > 16 ? 32 : 16);
+  return static_cast<size_t>(kMaxSplits) * rows * align_up(channels, 96) * 4;
+}
+
+static WsPlan plan_workspace(const rosaq_packed& p, int M, size_t channels_total = 0) {
   WsPlan w;
   const Canonical& c = p.c;
   const size_t mblocks = (static_cast<size_t>(M) + kMBlock - 1) / kMBlock;
@@ -41,6 +54,12 @@ static WsPlan plan_workspace(const rosaq_packed& p, int M) {
   if (c.q_mode == ROSAQ_Q_FULL) {
     w.xf_b = off; off += align_up(xf_bytes, 256);
   }
+  w.tickets = off; off += kTicketBytes;
+  w.required = off;
+  w.part = off;
+  const size_t widest = std::max<size_t>(channels_total ? channels_total : c.N,
+                                         c.q_mode == ROSAQ_Q_FULL ? c.D : 0);
+  off += align_up(part_room(M, widest), 256);
   w.total = off;
   return w;
 }
@@ -126,7 +145,7 @@ static int upload(rosaq_packed* p, const float* Q, hipStream_t st) {
   DeviceImage img;
   try {
     build_device_image(p->c, Q, &img);
-  } catch (const std::bad_alloc&) { return fail(ROSAQ_ERR_NOMEM, "out of host memory"); }
+  } catch (const std::exception&) { return fail(ROSAQ_ERR_NOMEM, "out of host memory"); }
   const Canonical& c = p->c;
   struct Part { const void* src; size_t bytes; void** dst; };
   void* d_perm = nullptr;
@@ -165,12 +184,15 @@ static int check_call(const rosaq_packed_t* p, const void* x, int32_t M, int64_t
                                          : "rosaq_linear does not serve a HEADWISE handle");
   if (M < 1) return fail(ROSAQ_ERR_SHAPE, "M must be at least 1");
   if (M > (1 << 20)) return fail(ROSAQ_ERR_SHAPE, "M above 2^20: split the call");
+  // the prologue kernels index the fragment copy of x with 32-bit integers (16 bytes per index)
+  if ((static_cast<int64_t>(M) + kMBlock - 1) / kMBlock * kMBlock * p->c.D / 8 > INT32_MAX)
+    return fail(ROSAQ_ERR_SHAPE, "M x in_features above 2^34: split the call");
   if (ldx < p->c.D || ldy < p->c.N) return fail(ROSAQ_ERR_SHAPE, "leading dimension smaller than width");
   if (reinterpret_cast<uintptr_t>(x) % 16 || ldx % 8)
     return fail(ROSAQ_ERR_ALIGN, "x must be 16-byte aligned and ldx a multiple of 8");
   if (reinterpret_cast<uintptr_t>(y) % 2) return fail(ROSAQ_ERR_ALIGN, "y must be 2-byte aligned");
   *plan = plan_workspace(*p, M);
-  if (!ws || ws_bytes < plan->total) return fail(ROSAQ_ERR_WORKSPACE, "workspace missing or too small");
+  if (!ws || ws_bytes < plan->required) return fail(ROSAQ_ERR_WORKSPACE, "workspace missing or too small");
   if (reinterpret_cast<uintptr_t>(ws) % 256) return fail(ROSAQ_ERR_ALIGN, "workspace must be 256-byte aligned");
   return ROSAQ_OK;
 }
@@ -183,7 +205,7 @@ static int check_device(const rosaq_packed_t* const* ps, int count) {
 
 // y_i = xhat W_i^T for `count` layers that share the xhat fragments in the workspace.
 static int run_main_gemm(const rosaq_packed_t* const* ps, int count, const WsPlan& w, int M,
-                         void* const* ys, const int64_t* ldys, char* ws, void* stream) {
+                         void* const* ys, const int64_t* ldys, char* ws, size_t ws_bytes, void* stream) {
   const Canonical& c = ps[0]->c;
   GemmArgs a{};
   a.xf = ws + (c.q_mode == ROSAQ_Q_FULL ? w.xf_b : w.xf_a);
@@ -196,17 +218,23 @@ static int run_main_gemm(const rosaq_packed_t* const* ps, int count, const WsPla
   a.M = M;
   a.ks_s = c.K / kKStep; a.G = c.G; a.KS = c.D / kKStep; a.KS_out = 0;
   a.bits = c.bits; a.out_frag = 0;
+  a.part = ws + w.part; a.part_bytes = ws_bytes > w.part ? ws_bytes - w.part : 0;
+  a.tickets = ws + w.tickets + kTicketsPerLaunch * sizeof(uint32_t); a.ticket_count = kTicketsPerLaunch;
   return launch_gemm(a, g_tune, stream);
 }
 
 // x -> xhat fragments in the workspace (gather / head-wise blocks / dense rotation).
 static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_dev, int M,
-                        int64_t ldx, char* ws, void* hip_stream) {
+                        int64_t ldx, char* ws, size_t ws_bytes, void* hip_stream) {
   const Canonical& c = p->c;
+  // the first launch of a call clears the tickets of the GEMM launches behind it
+  void* tickets = ws + w.tickets;
+  const int n_tickets = 2 * kTicketsPerLaunch;
   if (c.q_mode == ROSAQ_Q_HEADWISE)
-    return launch_rotate_headwise(x_dev, ldx, M, c.D, p->d_qf, p->d_pos, ws + w.xf_a, hip_stream);
+    return launch_rotate_headwise(x_dev, ldx, M, c.D, p->d_qf, p->d_pos, ws + w.xf_a, tickets, n_tickets,
+                                  hip_stream);
   if (c.q_mode == ROSAQ_Q_NONE)
-    return launch_gather(x_dev, ldx, M, c.D, p->d_perm, ws + w.xf_a, hip_stream);
+    return launch_gather(x_dev, ldx, M, c.D, p->d_perm, ws + w.xf_a, tickets, n_tickets, hip_stream);
   // xhat = x fp16(Q): a dense fp16 contraction, run as an all-fp16 layer whose
   // "weight" is Q^T with rows already in storage order
   GemmArgs a{};
@@ -214,9 +242,14 @@ static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_
   if (M <= 16) {
     a.xrow = x_dev;        // skinny input: the rotation reads x in place, no fragment copy
     a.ldx = ldx;
+    // no launch in front of the rotation: it runs unsplit and clears the main GEMM's tickets itself
+    a.zero_ptr = static_cast<char*>(tickets) + kTicketsPerLaunch * sizeof(uint32_t);
+    a.zero_count = kTicketsPerLaunch;
   } else {
-    const int rc = launch_gather(x_dev, ldx, M, c.D, nullptr, ws + w.xf_a, hip_stream);
+    const int rc = launch_gather(x_dev, ldx, M, c.D, nullptr, ws + w.xf_a, tickets, n_tickets, hip_stream);
     if (rc != ROSAQ_OK) return rc;
+    a.part = ws + w.part; a.part_bytes = ws_bytes > w.part ? ws_bytes - w.part : 0;
+    a.tickets = tickets; a.ticket_count = kTicketsPerLaunch;
   }
   a.nseg = 1;
   a.seg[0].wS = p->d_qf; a.seg[0].wq = nullptr;
@@ -228,14 +261,14 @@ static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_
 }
 
 static int run_call(const rosaq_packed_t* const* ps, int count, const void* x_dev, int M,
-                    int64_t ldx, void* const* ys, const int64_t* ldys, char* ws, const WsPlan& w,
-                    void* hip_stream) {
+                    int64_t ldx, void* const* ys, const int64_t* ldys, char* ws, size_t ws_bytes,
+                    const WsPlan& w, void* hip_stream) {
   if (g_tune_stages & 1) {
-    const int rc = run_prologue(ps[0], w, x_dev, M, ldx, ws, hip_stream);
+    const int rc = run_prologue(ps[0], w, x_dev, M, ldx, ws, ws_bytes, hip_stream);
     if (rc != ROSAQ_OK) return rc;
   }
   if (!(g_tune_stages & 2)) return ROSAQ_OK;
-  return run_main_gemm(ps, count, w, M, ys, ldys, ws, hip_stream);
+  return run_main_gemm(ps, count, w, M, ys, ldys, ws, ws_bytes, hip_stream);
 }
 
 static uint64_t fnv1a(uint64_t h, const void* data, size_t n) {
@@ -272,7 +305,7 @@ int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_pack
       if (rc != ROSAQ_OK) { delete p; return rc; }
     }
     rc = pack_host(*desc, &p->c, &err, on_device ? &rotated : nullptr);
-  } catch (const std::bad_alloc&) { rc = ROSAQ_ERR_NOMEM; err = "out of host memory"; }
+  } catch (const std::exception&) { rc = ROSAQ_ERR_NOMEM; err = "out of host memory"; }
   if (rc != ROSAQ_OK) { delete p; return fail(rc, err); }
   {
     uint64_t h = fnv1a(1469598103934665603ull, &desc->q_mode, sizeof(desc->q_mode));
@@ -327,13 +360,28 @@ size_t rosaq_workspace_bytes(const rosaq_packed_t* p, int32_t M) {
   return std::max<size_t>(plan_workspace(*p, M).total, 256);
 }
 
+size_t rosaq_workspace_bytes_min(const rosaq_packed_t* p, int32_t M) {
+  if (!p || M < 1) return 0;
+  return std::max<size_t>(plan_workspace(*p, M).required, 256);
+}
+
+size_t rosaq_workspace_bytes_batch(const rosaq_packed_t* const* layers, int32_t count, int32_t M) {
+  if (!layers || count < 1 || count > kMaxBatch || M < 1) return 0;
+  size_t channels = 0;
+  for (int i = 0; i < count; ++i) {
+    if (!layers[i]) return 0;
+    channels += align_up(static_cast<size_t>(layers[i]->c.N), kTileN);
+  }
+  return std::max<size_t>(plan_workspace(*layers[0], M, channels).total, 256);
+}
+
 int rosaq_linear(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t ldx, void* y_dev,
                  int64_t ldy, void* ws_dev, size_t ws_bytes, void* hip_stream) {
   WsPlan w;
   int rc = check_call(p, x_dev, M, ldx, y_dev, ldy, ws_dev, ws_bytes, false, &w);
   if (rc == ROSAQ_OK) rc = check_device(&p, 1);
   if (rc != ROSAQ_OK) return rc;
-  return run_call(&p, 1, x_dev, M, ldx, &y_dev, &ldy, static_cast<char*>(ws_dev), w, hip_stream);
+  return run_call(&p, 1, x_dev, M, ldx, &y_dev, &ldy, static_cast<char*>(ws_dev), ws_bytes, w, hip_stream);
 }
 
 int rosaq_linear_headwise(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t ldx,
@@ -343,7 +391,7 @@ int rosaq_linear_headwise(const rosaq_packed_t* p, const void* x_dev, int32_t M,
   int rc = check_call(p, x_dev, M, ldx, y_dev, ldy, ws_dev, ws_bytes, true, &w);
   if (rc == ROSAQ_OK) rc = check_device(&p, 1);
   if (rc != ROSAQ_OK) return rc;
-  return run_call(&p, 1, x_dev, M, ldx, &y_dev, &ldy, static_cast<char*>(ws_dev), w, hip_stream);
+  return run_call(&p, 1, x_dev, M, ldx, &y_dev, &ldy, static_cast<char*>(ws_dev), ws_bytes, w, hip_stream);
 }
 
 int rosaq_linear_batch(const rosaq_packed_t* const* layers, int32_t count, const void* x_dev,
@@ -367,7 +415,7 @@ int rosaq_linear_batch(const rosaq_packed_t* const* layers, int32_t count, const
     if (rc != ROSAQ_OK) return rc;
   }
   if (check_device(layers, count) != ROSAQ_OK) return ROSAQ_ERR_HOSTONLY;
-  return run_call(layers, count, x_dev, M, ldx, y_dev, ldy, static_cast<char*>(ws_dev), w, hip_stream);
+  return run_call(layers, count, x_dev, M, ldx, y_dev, ldy, static_cast<char*>(ws_dev), ws_bytes, w, hip_stream);
 }
 
 int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* K, int32_t* bits,
@@ -435,7 +483,7 @@ int rosaq_tune(const char* key, int32_t value) {
       return fail(ROSAQ_ERR_ARG, "wpb must be 0, 4, 8 or 16");
     g_tune.wpb = value; return ROSAQ_OK;
   }
-  if (!std::strncmp(key, "rot_", 4)) {
+  if (!std::strncmp(key, "rot_", 4) && std::strcmp(key, "rot_splits")) {
     const char* k = key + 4;
     if (value < 0 || value > 4 || value == 3) {
       if (!((std::strcmp(k, "depth") == 0 || std::strcmp(k, "nt") == 0) && value == 3))
@@ -449,6 +497,10 @@ int rosaq_tune(const char* key, int32_t value) {
   if (!std::strcmp(key, "depth")) {
     if (value < 0 || value > 4) return fail(ROSAQ_ERR_ARG, "depth must be 0 to 4");
     g_tune.depth = value; return ROSAQ_OK;
+  }
+  if (!std::strcmp(key, "splits") || !std::strcmp(key, "rot_splits")) {
+    if (value < 0 || value > kMaxSplits) return fail(ROSAQ_ERR_ARG, "splits must be 0 to 16");
+    (key[0] == 'r' ? g_tune_rot : g_tune).splits = value; return ROSAQ_OK;
   }
   if (!std::strcmp(key, "mt") || !std::strcmp(key, "nt")) {
     const bool wide = key[0] == 'n' && (value == 3 || value == 6);
@@ -468,8 +520,10 @@ int rosaq_launch_shape(int32_t M, int32_t channels, int32_t in_features, int32_t
   if (M < 1 || channels < 1 || channels % kTileN || in_features < kGroup || in_features % kGroup)
     return fail(ROSAQ_ERR_SHAPE, "M >= 1, channels a positive multiple of 16, in_features a positive multiple of 128");
   if (bits != 3 && bits != 4 && bits != 16) return fail(ROSAQ_ERR_ARG, "bits must be 3, 4 or 16");
-  const GemmShape s = pick_gemm_shape(M, channels / kTileN, in_features, bits, g_tune);
+  const GemmShape s = pick_gemm_shape(M, channels / kTileN, in_features, bits, g_tune,
+                                      part_room(M, channels), kTicketsPerLaunch);
   shape_out[0] = s.mt; shape_out[1] = s.nt; shape_out[2] = s.wpb; shape_out[3] = s.depth;
+  shape_out[4] = s.splits;
   return ROSAQ_OK;
 }
 
@@ -477,7 +531,9 @@ int rosaq_packed_image(const rosaq_packed_t* p, int32_t which, void* out_host, s
   if (!p || !bytes) return fail(ROSAQ_ERR_NULL, "handle or bytes is NULL");
   if (which != 0 && which != 1) return fail(ROSAQ_ERR_ARG, "which must be 0 (fp16 fragments) or 1 (low-bit records)");
   DeviceImage img;
-  build_device_image(p->c, nullptr, &img);
+  try {
+    build_device_image(p->c, nullptr, &img);
+  } catch (const std::exception&) { return fail(ROSAQ_ERR_NOMEM, "out of host memory"); }
   const std::vector<uint32_t>& v = which == 0 ? img.wS : img.wq;
   const size_t need = v.size() * sizeof(uint32_t);
   if (out_host) {

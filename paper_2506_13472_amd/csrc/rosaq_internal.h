@@ -69,18 +69,35 @@ struct GemmArgs {
   int KS_out;            // k-steps of the output when out is in fragment order
   int bits;              // 3 or 4 (ignored when G == 0)
   int out_frag;          // 0: y row-major, 1: xhat fragment order
+  // split-K across workgroups (optional): room for fp32 partial tiles and tile tickets.  A launch
+  // is split only if both fit; tickets must be zero before the launch and are zero after it.
+  void* part = nullptr;
+  size_t part_bytes = 0;
+  void* tickets = nullptr;
+  int ticket_count = 0;
+  void* zero_ptr = nullptr;   // 32-bit words this launch clears for a later launch of the call
+  int zero_count = 0;
 };
-struct GemmTune { int mt = 0, nt = 0, wpb = 0, depth = 0; };   // 0 = heuristic
-struct GemmShape { int mt, nt, wpb, depth; };
-GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tune);
+constexpr int kMaxSplits = 16;
+constexpr int kTicketsPerLaunch = 4096;   // ticket words per GEMM launch kept in the workspace
+struct GemmTune { int mt = 0, nt = 0, wpb = 0, depth = 0, splits = 0; };   // 0 = heuristic
+struct GemmShape { int mt, nt, wpb, depth, splits; };
+// `part_bytes` / `ticket_count`: what the caller can offer for split-K (0 = never split)
+GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tune,
+                          size_t part_bytes = 0, int ticket_count = 0, int ks_s = -1);
+// bytes of partial tiles a launch of this shape needs
+size_t gemm_part_bytes(const GemmShape& s, int M, int ntiles);
 int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream);
 // Host copy of the kernel's workgroup -> (channel chunk, row group) map: b < 0 returns the grid
 // size, otherwise 1 and the pair, or 0 for a padding workgroup that exits at once.
 int block_map_host(int b, int chunks, int mgroups, int* chunk, int* mg);
+// both prologue launchers also clear `zero_count` 32-bit words at `zero_ptr` (the tickets of the
+// GEMM launches that follow in the same call)
 int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_dev,
-                  void* xf, void* stream);
+                  void* xf, void* zero_ptr, int zero_count, void* stream);
 int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void* qh,
-                           const int32_t* pos_dev, void* xf, void* stream);
+                           const int32_t* pos_dev, void* xf, void* zero_ptr, int zero_count,
+                           void* stream);
 
 int launch_rotate_weights_f64(const void* W_dev, const void* Q_dev, void* out_dev, int N, int D,
                               int headwise, void* stream);

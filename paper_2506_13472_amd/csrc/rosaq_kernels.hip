@@ -104,22 +104,6 @@ struct GemmSeg {
   int N;
   int tile_end;      // exclusive prefix sum of the layers' valid channel tiles, ceil(N / 16)
 };
-// ROSAQ_PROBE_* macros: measurement variants of gemm_kernel (loads only, no weights, no
-// epilogue, ...), compiled into a separate library by build.py --probe; never defined in
-// the product build.
-#ifdef ROSAQ_PROBE_TIMELINE
-// per-wave shader-clock stamps of the last launch
-__device__ unsigned long long g_timeline[4096 * 16 * 8];
-#define ROSAQ_STAMP(i)                                                                  \
-  if (lane == 0 && blockIdx.x < 4096)                                                   \
-    g_timeline[(static_cast<size_t>(blockIdx.x) * 16 + wave) * 8 + (i)] = wall_clock64();
-extern "C" int rosaq_debug_timeline(void* host, size_t bytes) {
-  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timeline), bytes, 0, hipMemcpyDeviceToHost));
-}
-#else
-#define ROSAQ_STAMP(i)
-#endif
-
 struct GemmDev {
   const uint4* xf;
   const _Float16* xrow;   // all-fp16 launches only: read A fragments from row-major x instead of xf
@@ -127,7 +111,50 @@ struct GemmDev {
   GemmSeg seg[kMaxBatch];
   int nseg;
   int M, ks_s, G, KS, KS_out, out_frag, chunks, mgroups;
+  // split-K across workgroups: `splits` workgroups share one output tile, each over its own run
+  // of the contraction; their fp32 partial tiles meet in `part`, and the workgroup that draws
+  // the last ticket of a tile adds them up in split order and stores the result
+  int splits;
+  float4* part;            // [tiles][splits][MT * NT][64] float4
+  unsigned* tickets;       // [tiles], zero before the launch and zero again after it
+  unsigned* zero_ptr;      // words this launch clears for a later launch (may be null)
+  int zero_count;
 };
+
+// Partial tiles and tickets travel between workgroups that may sit on different XCDs, whose L2
+// caches do not see each other's lines.  They are therefore written and read with device-scope
+// relaxed atomics (64 bits at a time), which go past the non-coherent cache levels, instead of
+// a release / acquire pair, which on this chip writes back and invalidates a whole L2.
+__device__ __forceinline__ void store_device_scope(float4* p, float4 v) {
+  unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
+  const unsigned long long lo = static_cast<unsigned long long>(__builtin_bit_cast(uint32_t, v.x)) |
+                                (static_cast<unsigned long long>(__builtin_bit_cast(uint32_t, v.y)) << 32);
+  const unsigned long long hi = static_cast<unsigned long long>(__builtin_bit_cast(uint32_t, v.z)) |
+                                (static_cast<unsigned long long>(__builtin_bit_cast(uint32_t, v.w)) << 32);
+  __hip_atomic_store(q, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(q + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float4 load_device_scope(const float4* p) {
+  const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
+  const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float4(__builtin_bit_cast(float, static_cast<uint32_t>(lo)),
+                     __builtin_bit_cast(float, static_cast<uint32_t>(lo >> 32)),
+                     __builtin_bit_cast(float, static_cast<uint32_t>(hi)),
+                     __builtin_bit_cast(float, static_cast<uint32_t>(hi >> 32)));
+}
+
+// Split `s` of `splits` owns the units [u_lo, u_hi) of the fp16 k-steps and [g_lo, g_hi) of the
+// low-bit groups: the contraction is cut at multiples of total / splits k-steps (a group counts
+// as four), each cut moved to the nearest group boundary once it lies past the fp16 k-steps.
+__host__ __device__ __forceinline__ void split_cut(int s, int splits, int ks_s, int G, int& u, int& g) {
+  const int total = ks_s + 4 * G;
+  const int b = static_cast<int>(static_cast<long long>(s) * total / splits);
+  if (b <= ks_s) { u = b; g = 0; return; }
+  u = ks_s;
+  g = (b - ks_s + 2) >> 2;
+  if (g > G) g = G;
+}
 
 // Block -> (channel chunk, row group).  blockIdx % 8 is the XCD a workgroup lands on; each
 // XCD owns the chunks congruent to its number.  Inside an XCD consecutive workgroups, which
@@ -241,11 +268,14 @@ void gemm_kernel(GemmDev p) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int chunk, mg;
-  if (!map_block(blockIdx.x, p.chunks, p.mgroups, chunk, mg)) return;
-  ROSAQ_STAMP(0)
-#ifdef ROSAQ_PROBE_EMPTY
-  if (p.M > 0) return;
-#endif
+  // the workgroups of one output tile are neighbours on one XCD (blockIdx % 8 is the XCD)
+  const int splits = p.splits;
+  const int local = blockIdx.x >> 3;
+  const int split = splits > 1 ? local % splits : 0;
+  const int base_block = splits > 1 ? ((local / splits) << 3) | (blockIdx.x & 7) : blockIdx.x;
+  if (p.zero_ptr != nullptr && blockIdx.x == 0)
+    for (int i = threadIdx.x; i < p.zero_count; i += WPB * 64) p.zero_ptr[i] = 0u;
+  if (!map_block(base_block, p.chunks, p.mgroups, chunk, mg)) return;
   const int tile0 = chunk * NT;   // first tile of the chunk in the launch's tile list
   const int mtile0 = mg * MT;
   // where each of the chunk's tiles lives (uniform over the workgroup): fp16 fragments and
@@ -312,11 +342,6 @@ void gemm_kernel(GemmDev p) {
     for (int mt = 0; mt < MT; ++mt)
       r.a[mt] = row_ok ? xa[mt][static_cast<size_t>(u) * 256] : make_uint4(0, 0, 0, 0);
   };
-#ifdef ROSAQ_PROBE_NO_X
-#define ROSAQ_XLOAD(dst, src) dst = make_uint4(lane, 1, 2, 3)
-#else
-#define ROSAQ_XLOAD(dst, src) dst = src
-#endif
   auto compute_step = [&](const StepRegs& r) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -333,11 +358,7 @@ void gemm_kernel(GemmDev p) {
       constexpr int kCodeDwords = BITS == 4 ? 256 : 192, kRecDwords = kCodeDwords + 16;
       const uint32_t* rec = wq_t[nt] + static_cast<size_t>(g) * kRecDwords;
       if (BITS == 4) {
-#ifdef ROSAQ_PROBE_NO_W
-        const uint4 c = make_uint4(lane, 5, 6, 7);
-#else
         const uint4 c = reinterpret_cast<const uint4*>(rec)[lane];
-#endif
         r.cw[nt][0] = c.x; r.cw[nt][1] = c.y; r.cw[nt][2] = c.z; r.cw[nt][3] = c.w;
       } else {
         const Code3 c = reinterpret_cast<const Code3*>(rec)[lane];
@@ -352,20 +373,10 @@ void gemm_kernel(GemmDev p) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         r.a[t][mt] = make_uint4(0, 0, 0, 0);
-        if (row_ok) { ROSAQ_XLOAD(r.a[t][mt], xa[mt][(ks0 + t) * 256]); }
+        if (row_ok) r.a[t][mt] = xa[mt][(ks0 + t) * 256];
       }
   };
   auto compute_group = [&](const GroupRegs& r) {
-#ifdef ROSAQ_PROBE_NO_COMPUTE
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-          acc[nt][mt][t] += __builtin_bit_cast(float, r.cw[nt][t] ^ r.a[t][mt].x ^ r.a[t][mt].y ^ r.a[t][mt].z ^ r.a[t][mt].w ^ r.sz[nt]);
-    return;
-#endif
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       const half2v sz2 = as_h2(r.sz[nt]);
@@ -393,6 +404,12 @@ void gemm_kernel(GemmDev p) {
   };
 
   const int ks_s = p.ks_s, G = p.G;
+  // this workgroup's run of the contraction (everything when the launch is not split)
+  int u_lo = 0, u_hi = ks_s, g_lo = 0, g_hi = G;
+  if (splits > 1 && BITS != 16) {
+    split_cut(split, splits, ks_s, G, u_lo, g_lo);
+    split_cut(split + 1, splits, ks_s, G, u_hi, g_hi);
+  }
   if constexpr (BITS == 16) {
     // All-fp16 layer (the dense rotation, or K = D): no low-bit state, so the registers
     // go to deep prefetch.  Units are runs of four k-steps; leftover k-steps go one by one.
@@ -430,12 +447,16 @@ void gemm_kernel(GemmDev p) {
           for (int mt = 0; mt < MT; ++mt)
             acc[nt][mt] = mfma16(as_h8(r.a[t][mt]), as_h8(r.b[t][nt]), acc[nt][mt]);
     };
-    const int nquad = ks_s >> 2;
+    // split launches cut the run of quads evenly; leftover k-steps go to the last split
+    const int quads_all = ks_s >> 2;
+    const int q_lo = splits > 1 ? static_cast<int>(static_cast<long long>(split) * quads_all / splits) : 0;
+    const int q_hi = splits > 1 ? static_cast<int>(static_cast<long long>(split + 1) * quads_all / splits) : quads_all;
+    const int nquad = q_hi - q_lo;
     // fp16 tiles are a power-of-two number of KiB apart when D is: workgroups that all walk
     // their tiles from k = 0 would camp on the same HBM channels.  Each workgroup starts
     // its walk at its own offset (the sum over k does not care where it starts).
     const int skew = nquad ? (blockIdx.x * 5) % nquad : 0;
-    auto at = [&](int i) { const int v = i + skew; return v >= nquad ? v - nquad : v; };
+    auto at = [&](int i) { const int v = i + skew; return q_lo + (v >= nquad ? v - nquad : v); };
     QuadRegs q[DEPTH];
     int u = wave;
 #pragma unroll
@@ -450,56 +471,45 @@ void gemm_kernel(GemmDev p) {
         }
       }
     }
-    for (int st = 4 * nquad + wave; st < ks_s; st += WPB) {
-      StepRegs s0;
-      load_step(st, s0);
-      compute_step(s0);
-    }
+    if (split == splits - 1 || splits <= 1)
+      for (int st = 4 * quads_all + wave; st < ks_s; st += WPB) {
+        StepRegs s0;
+        load_step(st, s0);
+        compute_step(s0);
+      }
   } else {
-  int u = wave;
-  int g = (wave + WPB - ks_s % WPB) % WPB;
+  int u = u_lo + wave;
+  int g = g_lo + (wave + WPB - (u_hi - u_lo) % WPB) % WPB;
   StepRegs s0, s1;
   GroupRegs r[DEPTH];
-  if (u < ks_s) load_step(u, s0);
-  if (u + WPB < ks_s) load_step(u + WPB, s1);
+  if (u < u_hi) load_step(u, s0);
+  if (u + WPB < u_hi) load_step(u + WPB, s1);
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d)
-    if (g + d * WPB < G) load_group(g + d * WPB, r[d]);
-  for (; u < ks_s; u += 2 * WPB) {
+    if (g + d * WPB < g_hi) load_group(g + d * WPB, r[d]);
+  for (; u < u_hi; u += 2 * WPB) {
     compute_step(s0);
-    if (u + 2 * WPB < ks_s) load_step(u + 2 * WPB, s0);
-    if (u + WPB < ks_s) {
+    if (u + 2 * WPB < u_hi) load_step(u + 2 * WPB, s0);
+    if (u + WPB < u_hi) {
       compute_step(s1);
-      if (u + 3 * WPB < ks_s) load_step(u + 3 * WPB, s1);
+      if (u + 3 * WPB < u_hi) load_step(u + 3 * WPB, s1);
     }
   }
-  for (; g < G; g += DEPTH * WPB) {
+  for (; g < g_hi; g += DEPTH * WPB) {
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
-      if (g + d * WPB < G) {
+      if (g + d * WPB < g_hi) {
         compute_group(r[d]);
-#ifdef ROSAQ_PROBE_TIMELINE
-        if (d == 0 && g < WPB) { ROSAQ_STAMP(1) }
-#endif
-        if (g + (d + DEPTH) * WPB < G) load_group(g + (d + DEPTH) * WPB, r[d]);
+        if (g + (d + DEPTH) * WPB < g_hi) load_group(g + (d + DEPTH) * WPB, r[d]);
       }
     }
   }
   }   // BITS != 16
-  ROSAQ_STAMP(2)
 
-#ifdef ROSAQ_PROBE_NO_EPI
-  {
-    float t = 0.f;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) t += acc[nt][mt][0] + acc[nt][mt][1] + acc[nt][mt][2] + acc[nt][mt][3];
-    if (t == 12345.678f) p.seg[0].out[lane] = static_cast<_Float16>(t);
-    return;
-  }
-#endif
   // ---- sum the waves of this workgroup through LDS in wave order -----------------------
+  constexpr int kSlots = kRedNT * MT;
+  const size_t tile_id = static_cast<size_t>(chunk) * p.mgroups + mg;
+  float4* my_part = p.part + ((tile_id * splits + split) * (kRedPasses * kSlots)) * 64 + lane;
 #pragma unroll
   for (int pass = 0; pass < kRedPasses; ++pass) {
     if (pass > 0) __syncthreads();
@@ -511,9 +521,7 @@ void gemm_kernel(GemmDev p) {
         red[wave][nt * MT + mt][lane] = make_float4(v[0], v[1], v[2], v[3]);
       }
     __syncthreads();
-    if (pass == 0) { ROSAQ_STAMP(3) }
 
-    constexpr int kSlots = kRedNT * MT;
     for (int slot = wave; slot < kSlots; slot += WPB) {
       float4 v = red[0][slot][lane];
 #pragma unroll
@@ -521,10 +529,48 @@ void gemm_kernel(GemmDev p) {
         const float4 o = red[w][slot][lane];
         v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
       }
-      store_fragment(p, v, mtile0 + slot % MT, tile0 + pass * kRedNT + slot / MT, lane);
+      if (splits <= 1)
+        store_fragment(p, v, mtile0 + slot % MT, tile0 + pass * kRedNT + slot / MT, lane);
+      else
+        store_device_scope(my_part + static_cast<size_t>(pass * kSlots + slot) * 64, v);
     }
   }
-  ROSAQ_STAMP(4)
+  if (splits <= 1) return;
+
+  // ---- split launches: the workgroup that draws a tile's last ticket finishes the tile -----
+  // Every wave's partial stores have completed (the barrier waits for each wave's outstanding
+  // memory operations first) before one thread draws the ticket.  No workgroup waits for
+  // another: all but the last one are done here.
+  __shared__ unsigned ticket_lds;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's partial stores are done
+  __syncthreads();
+  if (threadIdx.x == 0)
+    ticket_lds = __hip_atomic_fetch_add(p.tickets + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (ticket_lds != static_cast<unsigned>(splits - 1)) return;
+  if (threadIdx.x == 0)
+    __hip_atomic_store(p.tickets + tile_id, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  constexpr int kAllSlots = kRedPasses * kSlots;
+  const float4* tile_part = p.part + (tile_id * splits * kAllSlots) * 64 + lane;
+  for (int slot = wave; slot < kAllSlots; slot += WPB) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    // eight partial tiles in flight at a time, added in split order: the sum does not depend
+    // on the order in which the workgroups arrived
+    for (int sp0 = 0; sp0 < splits; sp0 += 8) {
+      float4 o[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (sp0 + j < splits) {
+          const float4* src = tile_part + (static_cast<size_t>(sp0 + j) * kAllSlots + slot) * 64;
+          o[j] = load_device_scope(src);
+        }
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (sp0 + j < splits) { v.x += o[j].x; v.y += o[j].y; v.z += o[j].z; v.w += o[j].w; }
+    }
+    const int pass = slot / kSlots, sl = slot - pass * kSlots;
+    store_fragment(p, v, mtile0 + sl % MT, tile0 + pass * kRedNT + sl / MT, lane);
+  }
 }
 
 // xhat fragments from x by a column permutation (or identity): the prologue of
@@ -534,7 +580,10 @@ void gemm_kernel(GemmDev p) {
 // 16-byte loads; the others are gathered element by element.
 __global__ __launch_bounds__(256) void gather_kernel(const _Float16* __restrict__ x, int64_t ldx,
                                                      int M, int KS, const int32_t* __restrict__ perm,
-                                                     uint4* __restrict__ xf, int total) {
+                                                     uint4* __restrict__ xf, int total,
+                                                     unsigned* __restrict__ zero_ptr, int zero_count) {
+  if (blockIdx.x == 0)   // tickets of the GEMM launches that follow in this call
+    for (int i = threadIdx.x; i < zero_count; i += 256) zero_ptr[i] = 0u;
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
   const int lane = idx & 63, mt = (idx >> 6) & 3;
@@ -584,7 +633,10 @@ __global__ __launch_bounds__(256) void gather_kernel(const _Float16* __restrict_
 // the tile to the storage position of each rotated channel.
 __global__ __launch_bounds__(256) void rotate_headwise_kernel(
     const _Float16* __restrict__ x, int64_t ldx, int M, int KS, int H, const uint4* __restrict__ qh,
-    const int32_t* __restrict__ pos, _Float16* __restrict__ xf) {
+    const int32_t* __restrict__ pos, _Float16* __restrict__ xf, unsigned* __restrict__ zero_ptr,
+    int zero_count) {
+  if (blockIdx.x == 0 && blockIdx.y == 0)   // tickets of the GEMM launch that follows in this call
+    for (int i = threadIdx.x; i < zero_count; i += 256) zero_ptr[i] = 0u;
   const int lane = threadIdx.x & 63;
   const int mt = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // the eight column tiles of a head share x_h: keep them on one XCD (id % 8)
@@ -724,7 +776,7 @@ static int hip_fail(hipError_t e, const char* what) {
 
 template <int BITS, int MT, int NT, int WPB, int DEPTH>
 static int launch_gemm_t(const GemmDev& d, hipStream_t st) {
-  const int xblocks = map_grid(d.chunks, d.mgroups);
+  const int xblocks = map_grid(d.chunks, d.mgroups) * (d.splits > 1 ? d.splits : 1);
   hipLaunchKernelGGL((gemm_kernel<BITS, MT, NT, WPB, DEPTH>), dim3(xblocks), dim3(WPB * 64), 0, st, d);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "gemm_kernel launch");
@@ -735,7 +787,84 @@ static int launch_gemm_t(const GemmDev& d, hipStream_t st) {
 // tile's rows plus the tile's weights), VALU dequantisation (once per tile, so row
 // splitting repeats it) and MFMA.  The model below prices a tile by
 // max(inflow, VALU + MFMA) and the launch by the number of rounds of 256 tiles.
-GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tune) {
+size_t gemm_part_bytes(const GemmShape& s, int M, int ntiles) {
+  if (s.splits <= 1) return 0;
+  const size_t chunks = (ntiles + s.nt - 1) / s.nt, mgroups = ((M + 15) / 16 + s.mt - 1) / s.mt;
+  return chunks * mgroups * s.splits * (static_cast<size_t>(s.mt) * s.nt) * 1024;
+}
+
+// registers cap the units a wave can keep in flight
+static int clamp_depth(int mt, int nt, int wpb, int depth) {
+  int max_depth = 4;
+  if (wpb == 4) {
+    if (mt * nt == 16) max_depth = 3;
+  } else if (wpb == 8) {
+    if (mt * nt == 16) max_depth = 1;
+    else if (mt == 4) max_depth = 2;
+    else if (mt * nt == 8) max_depth = 3;
+  } else {
+    if (mt == 2) max_depth = 2;
+    else if (nt == 2) max_depth = 3;
+  }
+  return std::min(depth, max_depth);
+}
+
+static GemmShape pick_unsplit(int M, int ntiles, int D, int bits, const GemmTune& tune);
+
+// Split-K across workgroups (launches of up to 64 rows).  Measured on the 7B / 13B shapes at
+// M = 64, a split launch loses wherever the unsplit one already fills the chip: a 4096 x 4096 layer
+// takes 8.6 us as 256 tiles of 32 x 32 and 12.4 us as 64 tiles of 64 x 64 cut in 2, 3 or 4, because
+// the partial tiles, the ticket and the last workgroup's pass over the partials follow one
+// another at the end of a launch that is already bound by latency, not by bytes.  It wins where
+// whole 64-row tiles leave compute units idle over a long contraction: 13824 -> 5120 runs as
+// 160 workgroups of 32 x 64 in 25.9 us, as 80 x 3 workgroups of 64 x 64 in 22.4 us.  The default
+// therefore splits only such launches; rosaq_tune("splits", n) forces any count for tests.
+GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tune, size_t part_bytes,
+                          int ticket_count, int ks_s) {
+  GemmShape base = pick_unsplit(M, ntiles, D, bits, tune);
+  base.splits = 1;
+  const int mtiles = (M + 15) / 16;
+  if (tune.splits == 1 || part_bytes == 0 || ticket_count <= 0 || mtiles > 4) return base;
+  (void)ks_s;
+  const int mt = mtiles > 2 ? 4 : mtiles;                           // all rows in one workgroup
+  auto candidate = [&](int nt, int sp) {
+    GemmShape c{mt, nt, 8, 1, sp};
+    if (mt == 4 && nt == 6) c.wpb = 4;
+    c.depth = clamp_depth(c.mt, c.nt, c.wpb, tune.depth >= 1 ? tune.depth : 2);
+    if (nt == 3 || nt == 6) {
+      const int cap = mt == 4 ? 1 : (nt == 6 ? 2 : 3);
+      c.depth = std::min(tune.depth >= 1 ? tune.depth : (nt == 6 ? 1 : cap), cap);
+    }
+    if (bits == 16) {
+      const int per_unit = 16 * (c.mt + c.nt);
+      c.depth = tune.depth >= 1 && tune.depth <= 4 ? tune.depth : 3;
+      while (c.depth > 1 && c.depth * per_unit + 4 * c.mt * c.nt > 232) --c.depth;
+    }
+    return c;
+  };
+  auto fits = [&](const GemmShape& c) {
+    const int tiles = ((ntiles + c.nt - 1) / c.nt) * ((mtiles + c.mt - 1) / c.mt);
+    return tiles <= ticket_count && gemm_part_bytes(c, M, ntiles) <= part_bytes;
+  };
+  if (tune.splits > 1) {                                            // forced: tests and measurements
+    int nt = tune.nt ? tune.nt : 4;
+    if ((nt == 3 || nt == 6) && (mt < 2 || (bits == 16 && nt == 6))) nt = 4;
+    if (nt != 1 && nt != 2 && nt != 3 && nt != 4 && nt != 6) nt = 4;
+    if (bits == 16 && mt == 1 && nt == 3) nt = 4;
+    const GemmShape c = candidate(nt, tune.splits);
+    return fits(c) ? c : base;
+  }
+  const int unsplit_wgs = ((ntiles + base.nt - 1) / base.nt) * ((mtiles + base.mt - 1) / base.mt);
+  const int chunks = (ntiles + 3) / 4;
+  const int sp = std::min(4, 256 / std::max(chunks, 1));
+  if (bits != 16 && mtiles >= 3 && D >= 8192 && unsplit_wgs <= 192 && sp >= 2) {
+    const GemmShape c = candidate(4, sp);
+    if (fits(c)) return c;
+  }
+  return base;
+}
+
+static GemmShape pick_unsplit(int M, int ntiles, int D, int bits, const GemmTune& tune) {
   GemmShape s;
   const int mtiles = (M + 15) / 16;
   const double k = static_cast<double>(D);
@@ -847,16 +976,14 @@ GemmShape pick_gemm_shape(int M, int ntiles, int D, int bits, const GemmTune& tu
   return s;
 }
 
-int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
+// 0 = launched, 1 = no kernel is instantiated for this shape, negative = error
+static int launch_gemm_shape(const GemmArgs& a, const GemmShape& sh, void* stream) {
   GemmDev d;
   d.xf = static_cast<const uint4*>(a.xf);
   d.xrow = static_cast<const _Float16*>(a.xrow);
   d.ldx = a.ldx;
   d.M = a.M; d.ks_s = a.ks_s; d.G = a.G; d.KS = a.KS; d.KS_out = a.KS_out;
   d.out_frag = a.out_frag;
-  int tiles_total = 0;
-  for (int i = 0; i < a.nseg; ++i) tiles_total += (a.seg[i].N + kTileN - 1) / kTileN;
-  const GemmShape sh = pick_gemm_shape(a.M, tiles_total, a.KS * kKStep, a.G == 0 ? 16 : a.bits, tune);
   d.nseg = a.nseg;
   int tiles = 0;   // valid channel tiles of all layers, in launch order
   for (int i = 0; i < kMaxBatch; ++i) {
@@ -871,6 +998,11 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
   }
   d.chunks = (tiles + sh.nt - 1) / sh.nt;
   d.mgroups = ((a.M + 15) / 16 + sh.mt - 1) / sh.mt;
+  d.splits = sh.splits;
+  d.part = static_cast<float4*>(a.part);
+  d.tickets = static_cast<unsigned*>(a.tickets);
+  d.zero_ptr = static_cast<unsigned*>(a.zero_ptr);
+  d.zero_count = a.zero_count;
   const int bits = a.G == 0 ? 16 : a.bits;
   hipStream_t st = static_cast<hipStream_t>(stream);
 #define ROSAQ_CASE(B, MT_, NT_, W)                                              \
@@ -896,8 +1028,25 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
 #undef ROSAQ_WIDE
 #undef ROSAQ_CASES
 #undef ROSAQ_CASE
-  set_error("no kernel for this bits / tile combination");
-  return ROSAQ_ERR_ARG;
+  return 1;
+}
+
+int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
+  int tiles_total = 0;
+  for (int i = 0; i < a.nseg; ++i) tiles_total += (a.seg[i].N + kTileN - 1) / kTileN;
+  const int bits = a.G == 0 ? 16 : a.bits;
+  auto shape = [&](const GemmTune& t) {
+    return pick_gemm_shape(a.M, tiles_total, a.KS * kKStep, bits, t, a.part ? a.part_bytes : 0,
+                           a.tickets ? a.ticket_count : 0, a.ks_s);
+  };
+  int rc = launch_gemm_shape(a, shape(tune), stream);
+  // a forced combination that no kernel is built for falls back to the heuristic's choice
+  if (rc == 1) rc = launch_gemm_shape(a, shape(GemmTune{}), stream);
+  if (rc == 1) {
+    set_error("no kernel for this bits / tile combination");
+    return ROSAQ_ERR_ARG;
+  }
+  return rc;
 }
 
 int launch_rotate_weights_f64(const void* W_dev, const void* Q_dev, void* out_dev, int N, int D,
@@ -920,23 +1069,24 @@ int launch_stream_probe(const void* src, const void* shared, int workgroups, int
 }
 
 int launch_gather(const void* x, int64_t ldx, int M, int D, const int32_t* perm_dev, void* xf,
-                  void* stream) {
+                  void* zero_ptr, int zero_count, void* stream) {
   const int KS = D / kKStep, mblocks = (M + kMBlock - 1) / kMBlock;
   const int total = mblocks * KS * 256;
   hipLaunchKernelGGL(gather_kernel, dim3((total + 255) / 256), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<const _Float16*>(x), ldx, M, KS,
-                     perm_dev, static_cast<uint4*>(xf), total);
+                     perm_dev, static_cast<uint4*>(xf), total, static_cast<unsigned*>(zero_ptr), zero_count);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "gather_kernel launch");
 }
 
 int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void* qh,
-                           const int32_t* pos_dev, void* xf, void* stream) {
+                           const int32_t* pos_dev, void* xf, void* zero_ptr, int zero_count,
+                           void* stream) {
   const int H = D / kHeadDim, mblocks = (M + kMBlock - 1) / kMBlock;
   hipLaunchKernelGGL(rotate_headwise_kernel, dim3(((H + 7) / 8) * 64, mblocks), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<const _Float16*>(x), ldx, M,
                      D / kKStep, H, static_cast<const uint4*>(qh), pos_dev,
-                     static_cast<_Float16*>(xf));
+                     static_cast<_Float16*>(xf), static_cast<unsigned*>(zero_ptr), zero_count);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? ROSAQ_OK : hip_fail(e, "rotate_headwise_kernel launch");
 }

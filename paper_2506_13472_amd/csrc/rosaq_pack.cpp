@@ -2,10 +2,14 @@
 // weight, pick the salient channels, quantise the rest group by group, and lay
 // the result out in the order the gfx950 kernels read it.  Pure C++, no GPU calls.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <functional>
+#include <exception>
+#include <mutex>
 #include <numeric>
+#include <system_error>
 #include <thread>
 
 #include "rosaq_internal.h"
@@ -59,19 +63,38 @@ void tile_kernel(const double* a, int lda, const double* b, int ldb, double* o, 
   }
 }
 
+// Runs fn over [0, n) in slices on up to 32 threads.  An exception thrown by a slice (an
+// allocation that fails) is carried to the calling thread and thrown again there after every
+// thread has joined; if a thread cannot be started the remaining rows run on the calling thread.
 void parallel_rows(int n, const std::function<void(int, int)>& fn) {
   unsigned hw = std::thread::hardware_concurrency();
   int nt = static_cast<int>(std::min<unsigned>(hw ? hw : 1u, 32u));
   nt = std::max(1, std::min(nt, n / 4 > 0 ? n / 4 : 1));
   if (nt == 1) { fn(0, n); return; }
   std::vector<std::thread> th;
+  std::exception_ptr first;
+  std::mutex mu;
+  auto guarded = [&](int lo, int hi) {
+    try {
+      fn(lo, hi);
+    } catch (...) {
+      std::lock_guard<std::mutex> lock(mu);
+      if (!first) first = std::current_exception();
+    }
+  };
   const int chunk = (n + nt - 1) / nt;
   for (int t = 0; t < nt; ++t) {
     const int lo = t * chunk, hi = std::min(n, lo + chunk);
     if (lo >= hi) break;
-    th.emplace_back(fn, lo, hi);
+    try {
+      th.emplace_back(guarded, lo, hi);
+    } catch (const std::system_error&) {
+      guarded(lo, n);   // no more threads: finish here
+      break;
+    }
   }
   for (auto& t : th) t.join();
+  if (first) std::rethrow_exception(first);
 }
 
 // Dense rotation: out [N x D] fp64 = W (fp16) * Q (fp32 [D x D] row-major).
@@ -162,14 +185,16 @@ int pack_host(const rosaq_pack_desc& d, Canonical* c, std::string* err,
     try {
       if (d.q_mode == ROSAQ_Q_FULL) rotate_full(d, &rot); else rotate_headwise(d, &rot);
     } catch (const std::bad_alloc&) { *err = "out of host memory"; return ROSAQ_ERR_NOMEM; }
-    bool bad = false;
+    std::atomic<bool> bad{false};
     parallel_rows(N, [&](int lo, int hi) {
+      bool local_bad = false;
       for (size_t i = static_cast<size_t>(lo) * D; i < static_cast<size_t>(hi) * D; ++i) {
         what_rw[i] = f64_to_f16(rot[i]);
-        if (((what_rw[i] >> 10) & 31) == 31) bad = true;
+        if (((what_rw[i] >> 10) & 31) == 31) local_bad = true;
       }
+      if (local_bad) bad.store(true, std::memory_order_relaxed);
     });
-    if (bad) { *err = "rotated weight overflows fp16"; return ROSAQ_ERR_NONFINITE; }
+    if (bad.load()) { *err = "rotated weight overflows fp16"; return ROSAQ_ERR_NONFINITE; }
   }
   const std::vector<uint16_t>& what = rotated16 ? *rotated16 : what_local;
 

@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cmath>
 #include <numeric>
+#include <string>
 #include <vector>
 
 #include "rosaq_internal.h"
@@ -87,15 +88,18 @@ __global__ __launch_bounds__(1024) void jacobi128_kernel(const double* __restric
   const double norm2 = block_sum(part);
   const double tiny = 2.220446049250313e-16 * sqrt(norm2) / kH;
   int sweep = 0;
+  int converged = norm2 > 0.0 ? 0 : 1;
   if (norm2 > 0.0) {
-    for (; sweep < max_sweeps; ++sweep) {
+    // the test runs before every sweep and once more after the last one
+    for (;; ++sweep) {
       part = 0.0;
       for (int i = tid; i < kH * kH; i += 1024) {
         const int r = i >> 7, c = i & 127;
         if (r != c) { const double a = A[r * kLd + c]; part += a * a; }
       }
       const double off2 = block_sum(part);
-      if (off2 <= tol * tol * norm2) break;
+      if (off2 <= tol * tol * norm2) { converged = 1; break; }
+      if (sweep == max_sweeps) break;
       for (int round = 0; round < kH - 1; ++round) {
         // tournament: player 127 stays, players 0..126 rotate; slot k meets slot 127 - k
         if (tid < 64) {
@@ -143,7 +147,7 @@ __global__ __launch_bounds__(1024) void jacobi128_kernel(const double* __restric
     }
   }
   if (tid < kH) lam_out[h * kH + tid] = A[tid * kLd + tid];
-  if (tid == 0) sweeps_out[h] = sweep;
+  if (tid == 0) sweeps_out[h] = converged ? sweep : -1;
 }
 
 static int pca_fail(hipError_t e, const char* what) {
@@ -193,9 +197,9 @@ int pca_headwise_device(const void* X_dev, int n_cal, int D, int64_t ldx, float*
   if (dS) (void)hipFree(dS);
   if (e != hipSuccess) return pca_fail(e, "rosaq_pca_headwise");
   for (int h = 0; h < H; ++h)
-    if (sweeps[h] >= 60) {
-      set_error("Jacobi did not converge within 60 sweeps");
-      return ROSAQ_ERR_NONFINITE;
+    if (sweeps[h] < 0) {
+      set_error("Jacobi did not converge within 60 sweeps (head " + std::to_string(h) + ")");
+      return ROSAQ_ERR_NOCONVERGE;
     }
   for (int h = 0; h < H; ++h) {
     const double* Vh = &V[static_cast<size_t>(h) * kH * kH];

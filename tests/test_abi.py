@@ -85,9 +85,12 @@ def test_call_argument_errors_on_host_only_handle():
     p = B.rosaq_pack_weights(W, Q, lam, K, bits, mode, host_only=True)
     assert (p.N, p.D, p.K, p.bits, p.group, p.q_mode) == (16, 256, 128, 4, 128, 0)
     assert p.device_bytes == 0
-    ws = B.rosaq_workspace_bytes(p, 4)
-    assert ws >= 256 and ws % 256 == 0
-    assert B.rosaq_workspace_bytes(p, 0) == 0
+    ws_full = B.rosaq_workspace_bytes(p, 4)
+    ws = B.rosaq_workspace_bytes_min(p, 4)      # the full size adds room for split launches
+    assert ws >= 256 and ws % 256 == 0 and ws_full % 256 == 0 and ws_full >= ws + 16 * 16 * 16 * 4
+    assert B.rosaq_workspace_bytes_batch([p, p], 4) >= ws_full
+    assert B.rosaq_workspace_bytes(p, 0) == 0 and B.rosaq_workspace_bytes_min(p, 0) == 0
+    assert B.rosaq_workspace_bytes(p, 65) == B.rosaq_workspace_bytes_min(p, 65)   # no splits above 64 rows
     X, Y, WS = 0x1000, 0x2000, 0x4000      # never dereferenced: every call fails validation first
     assert _code(lambda: B.rosaq_linear(p, 0, 4, 256, Y, 16, WS, ws)) == -1
     assert _code(lambda: B.rosaq_linear(p, X, 0, 256, Y, 16, WS, ws)) == -2
@@ -212,11 +215,16 @@ def test_launch_shape_of_the_named_workloads():
     assert shape(4096, 4096, 4096, 4)[:3] == (4, 4, 8)
     assert shape(2048, 13824, 5120, 4)[:3] == (4, 4, 8)
     # single rows: one 16x16 tile and sixteen waves per workgroup
-    assert shape(1, 4096, 4096, 4) == (1, 1, 16, 1)
+    assert shape(1, 4096, 4096, 4) == (1, 1, 16, 1, 1)
     # two tiles per workgroup in a launch of less than one round (13B down projection): sixteen waves too;
     # launches of several rounds keep eight
-    assert shape(1, 5120, 13824, 4) == (1, 2, 16, 2)
-    assert shape(1, 13824, 5120, 4) == (1, 2, 8, 2)
+    assert shape(1, 5120, 13824, 4) == (1, 2, 16, 2, 1)
+    assert shape(1, 13824, 5120, 4) == (1, 2, 8, 2, 1)
+    # the contraction is split over workgroups only where whole 64-row tiles would leave the chip
+    # under-filled over a long contraction: the 13B down projection runs as 80 tiles x 3 splits
+    assert shape(64, 5120, 13824, 4) == (4, 4, 8, 1, 3)
+    assert shape(64, 4096, 4096, 4)[4] == 1 and shape(64, 3 * 4096, 4096, 4)[4] == 1
+    assert shape(64, 4096, 11008, 3)[4] == 1 and shape(256, 5120, 13824, 4)[4] == 1
     # all-fp16 layers (the dense rotation) never get the 48- or 96-channel tiles
     assert shape(64, 4096, 4096, 16)[1] in (1, 2, 4)
     # overrides go through
@@ -225,6 +233,13 @@ def test_launch_shape_of_the_named_workloads():
         assert shape(64, 4096, 4096, 3)[:2] == (2, 6)
     finally:
         B.rosaq_tune("mt", 0); B.rosaq_tune("nt", 0)
+    B.rosaq_tune("splits", 5)
+    try:
+        assert shape(64, 4096, 4096, 4) == (4, 4, 8, 1, 5)
+        assert shape(16, 4096, 4096, 4)[::4] == (1, 5)
+        assert shape(65, 4096, 4096, 4)[4] == 1            # never above 64 rows
+    finally:
+        B.rosaq_tune("splits", 0)
     for bad in ((0, 4096, 4096, 4), (64, 4090, 4096, 4), (64, 4096, 4000, 4)):
         with pytest.raises(B.RosaqError) as e:
             shape(*bad)

@@ -140,3 +140,51 @@ def test_rosaq_beats_plain_rtn_on_heavy_tailed_inputs():
     e_rosaq = O.quality_report(lay["x"], lay["W"], Q32, O.pack(lay["W"], Q32, lam, 128, 4, O.MODE_FULL))
     e_rtn = O.quality_report(lay["x"], lay["W"], Q32, O.pack(lay["W"], Q32, lam, 0, 4, O.MODE_FULL))
     assert e_rosaq < e_rtn
+
+
+def _handmade_packed(W_S, codes, scales, zeros, group):
+    """A packed layer written out by hand (no call of O.pack): K fp16 columns, then one group."""
+    N, K = W_S.shape
+    D = K + codes.shape[1]
+    return dict(N=N, D=D, K=K, bits=4, group=group, mode=O.MODE_NONE,
+                salient_idx=np.arange(K, dtype=np.int32), perm=np.arange(D, dtype=np.int32),
+                W_S=W_S.astype(np.float16), codes=codes.astype(np.uint8),
+                scales=scales.astype(np.float16), zeros=zeros.astype(np.float16))
+
+
+def test_tolerance_scale_hand_computed():
+    # The max-error bound divides by ||x_row||_2 * ||w_col||_2 (w_col: the stored, dequantised
+    # weights of one output channel).  2 rows of x, 3 output channels, D = 4 (K = 2 fp16
+    # columns + one group of 2 codes), every number worked out by hand:
+    #   channel 0: W_S (3, 0), codes (4, 1), z 1, s 0.5 -> (1.5, 0)   norm sqrt(9 + 2.25) = 3.354101966
+    #   channel 1: W_S (0, 0), codes (2, 2), z 2, s 2   -> (0, 0)     norm 0
+    #   channel 2: W_S (1, 2), codes (0, 6), z 2, s 1   -> (-2, 4)    norm sqrt(1+4+4+16) = 5
+    #   x rows: (3, 4, 0, 0) norm 5;  (1, 1, 1, 1) norm 2
+    p = _handmade_packed(np.array([[3, 0], [0, 0], [1, 2]]), np.array([[4, 1], [2, 2], [0, 6]]),
+                         np.array([[0.5], [2.0], [1.0]]), np.array([[1], [2], [2]]), group=2)
+    x = np.array([[3, 4, 0, 0], [1, 1, 1, 1]], dtype=np.float16)
+    want = np.array([[5 * 3.3541019662496847, 0.0, 25.0], [2 * 3.3541019662496847, 0.0, 10.0]])
+    got = O.tolerance_scale(x, p)
+    assert got.shape == (2, 3)
+    assert np.allclose(got, want, rtol=1e-14, atol=0)
+
+
+def test_tolerance_scale_square_case_axes():
+    # M = N = D = 4: every axis has the same length, so a norm taken along the wrong axis, or an
+    # outer product the wrong way round, would still broadcast.  Row norms, column norms and the
+    # two factors are all different, so each such mistake changes the result.
+    W_S = np.array([[1, 0, 0], [0, 2, 0], [2, 2, 1], [0, 0, 0]])
+    codes = np.array([[0], [0], [0], [9]]); zeros = np.array([[0], [0], [0], [1]])
+    scales = np.array([[1.0], [1.0], [1.0], [0.5]])            # last column dequantises to (0, 0, 0, 4)
+    p = _handmade_packed(W_S, codes, scales, zeros, group=1)
+    x = np.array([[4, 0, 0, 3], [0, 0, 0, 0], [6, 8, 0, 0], [1, 2, 2, 0]], dtype=np.float16)
+    got = O.tolerance_scale(x, p)
+    xn = np.array([5.0, 0.0, 10.0, 3.0])          # norms of the rows of x
+    wn = np.array([1.0, 2.0, 3.0, 4.0])           # norms of the rows of the stored weight
+    assert got.shape == (4, 4)
+    for m in range(4):
+        for n in range(4):
+            assert got[m, n] == pytest.approx(xn[m] * wn[n], rel=1e-14, abs=0)
+    # the transposed outer product and the column norms (sqrt 5, sqrt 8, 1, 4) give other numbers
+    assert not np.allclose(got, got.T)
+    assert not np.allclose(got[0], 5.0 * np.array([np.sqrt(5), np.sqrt(8), 1.0, 4.0]))

@@ -160,16 +160,37 @@ def test_selection_rules_by_definition():
     assert sal.tolist() == list(range(32)) + list(range(128, 160))
 
 
+def test_top_and_bottom_is_the_union_of_top_and_bottom():
+    # salient-channel ablation appendix: the combined scheme takes both the channels Top selects
+    # and the channels Bottom selects.  With K' per side that is the rule called with K = 2 K'
+    # (K always counts the fp16 block), checked here against the two rules run on their own.
+    rng = np.random.default_rng(5)
+    lam = rng.random(384)
+    for k_side in (32, 64, 128):
+        top, _ = O.select_salient(lam, k_side, O.RULE_TOP)
+        bottom, _ = O.select_salient(lam, k_side, O.RULE_BOTTOM)
+        both, perm = O.select_salient(lam, 2 * k_side, O.RULE_TOP_AND_BOTTOM)
+        assert both.tolist() == sorted(set(top.tolist()) | set(bottom.tolist()))
+        assert len(both) == 2 * k_side and perm[:2 * k_side].tolist() == both.tolist()
+
+
 def test_top_rule_beats_the_ablation_rules_on_output_error():
     # synthetic analogue of the paper's salient-channel ablation: keeping the top-eigenvalue
     # channels in fp16 gives a smaller output error than bottom / a consecutive block elsewhere
-    lay = synth.make_layer(3, 32, 256, 48, 512)
+    lay = synth.make_layer(3, 32, 384, 48, 512)
     Q, lam = O.pca_full(lay["X_cal"], "jacobi")
     Q32 = Q.astype(np.float32)
     err = {}
-    for name, rule, arg in (("top", O.RULE_TOP, 0), ("bottom", O.RULE_BOTTOM, 0),
-                            ("block", O.RULE_CONSECUTIVE, 100), ("both", O.RULE_TOP_AND_BOTTOM, 0)):
-        p = O.pack(lay["W"], Q32, lam, 128, 3, O.MODE_FULL, rule=rule, arg=arg)
+    for name, rule, arg, K in (("top", O.RULE_TOP, 0, 128), ("bottom", O.RULE_BOTTOM, 0, 128),
+                               ("block", O.RULE_CONSECUTIVE, 150, 128),
+                               ("both_as_in_the_paper", O.RULE_TOP_AND_BOTTOM, 0, 256),
+                               ("both_same_budget", O.RULE_TOP_AND_BOTTOM, 0, 128)):
+        p = O.pack(lay["W"], Q32, lam, K, 3, O.MODE_FULL, rule=rule, arg=arg)
         err[name] = O.quality_report(lay["x"], lay["W"], Q32, p)
     assert err["top"] < err["bottom"] and err["top"] < err["block"]
-    assert err["top"] < err["both"] < err["bottom"]       # the ordering of the paper's ablation table
+    # the paper's table: Top & Bottom (both sets, 2 K channels in fp16) lands next to Top, far from
+    # Bottom; the extra K bottom channels carry almost no energy, so they buy next to nothing
+    assert err["both_as_in_the_paper"] < err["bottom"]
+    assert abs(err["both_as_in_the_paper"] - err["top"]) < 0.25 * err["top"]
+    # with the fp16 budget held at K (K/2 + K/2) the bottom half is wasted: worse than Top
+    assert err["top"] < err["both_same_budget"] < err["bottom"]
