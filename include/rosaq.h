@@ -146,6 +146,20 @@ int rosaq_linear_headwise(const rosaq_packed_t* p, const void* x_dev, int32_t M,
                           void* y_dev, int64_t ldy, void* ws_dev, size_t ws_bytes,
                           void* hip_stream);
 
+/* rosaq_linear_headwise_static - rosaq_linear_headwise for callers that cannot allocate or hold
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * The rotated activations, tickets and partial tiles go to a fixed 8 MiB array that the library
+ * keeps in the device memory of every GPU it runs on (until the process ends); the call itself
+ * allocates nothing.  Same arguments, rules and results as rosaq_linear_headwise, minus the
+ * workspace.  Limit: the call must fit the array, i.e. rosaq_workspace_bytes_min(p, M) <= 8 MiB
+ * (ceil(M / 64) * 128 * in_features bytes plus 32 KiB; M up to 960 at in_features 4096), else
+ * ROSAQ_ERR_WORKSPACE.  All calls on one GPU share that GPU's array: calls that overlap in time
+ * on one GPU (two streams, two threads) race and give wrong results; calls on one stream are safe.
+ * Errors: those of rosaq_linear_headwise. */
+#define ROSAQ_STATIC_SCRATCH_BYTES (8u << 20)
+int rosaq_linear_headwise_static(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t ldx,
+                                 void* y_dev, int64_t ldy, void* hip_stream);
+
 /* rosaq_linear_batch - up to 4 layers that read the same input through the same
  * rotation, in one pass: y_i = (x Q) What_i^T.  The query, key and value projections
  * of an attention block share their input activations and hence their PCA (Eq. 5 feeds

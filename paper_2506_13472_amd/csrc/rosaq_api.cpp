@@ -394,6 +394,28 @@ int rosaq_linear_headwise(const rosaq_packed_t* p, const void* x_dev, int32_t M,
   return run_call(&p, 1, x_dev, M, ldx, &y_dev, &ldy, static_cast<char*>(ws_dev), ws_bytes, w, hip_stream);
 }
 
+int rosaq_linear_headwise_static(const rosaq_packed_t* p, const void* x_dev, int32_t M, int64_t ldx,
+                                 void* y_dev, int64_t ldy, void* hip_stream) {
+  if (!p) return fail(ROSAQ_ERR_NULL, "handle is NULL");
+  if (M < 1) return fail(ROSAQ_ERR_SHAPE, "M must be at least 1");
+  // the size test comes first: it needs no GPU
+  const WsPlan need = plan_workspace(*p, M);
+  if (need.required > kStaticScratchBytes)
+    return fail(ROSAQ_ERR_WORKSPACE, "call needs more scratch than the library's static 8 MiB: use "
+                                     "rosaq_linear_headwise with a workspace");
+  // the address is only compared against NULL and alignment until the handle has passed its checks
+  WsPlan w;
+  void* probe = reinterpret_cast<void*>(uintptr_t{256});
+  int rc = check_call(p, x_dev, M, ldx, y_dev, ldy, probe, kStaticScratchBytes, true, &w);
+  if (rc == ROSAQ_OK) rc = check_device(&p, 1);
+  if (rc != ROSAQ_OK) return rc;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != ROSAQ_OK) return rc;
+  const size_t ws_bytes = std::min(w.total, kStaticScratchBytes);
+  return run_call(&p, 1, x_dev, M, ldx, &y_dev, &ldy, static_cast<char*>(ws), ws_bytes, w, hip_stream);
+}
+
 int rosaq_linear_batch(const rosaq_packed_t* const* layers, int32_t count, const void* x_dev,
                        int32_t M, int64_t ldx, void* const* y_dev, const int64_t* ldy,
                        void* ws_dev, size_t ws_bytes, void* hip_stream) {

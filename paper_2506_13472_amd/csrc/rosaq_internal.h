@@ -107,6 +107,11 @@ int launch_stream_probe(const void* src, const void* shared, int workgroups, int
 int pca_headwise_device(const void* X_dev, int n_cal, int D, int64_t ldx, float* Q_host,
                         double* eig_host, void* stream);
 
+// Library-owned scratch (rosaq_static.hip): the device address of this GPU's copy of a fixed
+// kStaticScratchBytes array, looked up once per device.
+constexpr size_t kStaticScratchBytes = size_t{8} << 20;
+int static_scratch(void** ptr_out);
+
 void set_error(const std::string& s);
 
 }  // namespace rosaq
