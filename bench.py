@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused ROSAQ linear on one MI355X.
 
-Workload (`config.workload` = "llama7b_attn_qkvo_M64_int4_headwise"): the four
+Headline workload (`config.workload` = "llama7b_attn_qkvo_M64_int4_headwise"): the four
 attention projections q/k/v/o of a LLaMA-7B-shaped layer, D = N = 4096, 32 heads
 x 128, x [64 x 4096] fp16, K = 128 FP16 salient channels, INT4 g128 for the rest,
 head-wise block-diagonal rotation.  One step = one decode step of the attention
@@ -12,10 +12,16 @@ issues four separate rosaq_linear_headwise calls instead).  The calls cycle over
 `--layers` x 4 distinct packed weights whose total size exceeds the 256 MB
 last-level cache, so every linear streams its weights from HBM.
 
-Prints ONE JSON line; `value` is algorithmic GB/s over the timed steps with all
-inputs resident in HBM.  Weights, activations and the 512-row calibration sets are
-synthetic (seeded); the rotations are the head-wise PCA of the calibration sets,
-computed on the GPU by rosaq_pca_headwise before the timed region.
+Prints ONE JSON line; `value` is algorithmic GB/s from the median step time with all
+inputs resident in HBM.  Every step is timed with its own pair of HIP events on the
+stream the kernels run on; median, p10 and p90 are reported (the paper's throughput
+appendix defines decode speed from the median time per token).  The same line carries
+two more measurements, each bounded to a few seconds of GPU time:
+  "sweep"   the M = 64 calls of the INT3 7B MLP and of the INT4 13B MLP (single calls)
+  "decode"  the 7 linears x 32 layers of a 7B-shaped decode step, 256 steps, against fp16 GEMMs
+Weights, activations and the 512-row calibration sets are synthetic (seeded); the head-wise
+rotations are the PCA of the calibration sets, computed on the GPU by rosaq_pca_headwise
+before the timed region; dense rotations are seeded random orthogonal matrices.
 """
 from __future__ import annotations
 
@@ -39,16 +45,73 @@ HEADS = 32
 CALLS_PER_STEP = 128
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes one launch of the main GEMM moves, from rocprofv3 FETCH_SIZE (KiB, x 2.0: the factor a
+# 256 MiB device copy gives for this counter) and WRITE_SIZE (KiB, x 1.0), keyed by what the launch
+# is: (layers in the launch, mt, nt, waves, depth, splits) as rosaq_launch_shape reports it.
+# Source: profiles/gemm_kernel_llama7b_attn_M64_int4.md.  A launch shape without an entry reports
+# traffic = null rather than another shape's number.
+MEASURED_TRAFFIC_KIB = {
+    (1, 2, 2, 8, 1, 1): (13640, 512),     # one 4096 x 4096 layer, 32 x 32 tiles
+    (3, 4, 3, 8, 1, 1): (32612, 1536),    # q, k, v in one launch, 64 x 48 tiles
+}
+
+
+def row_bytes(d_in, bits):
+    """Stored bytes of one output row: fp16 salient block, codes, fp16 scale + zero per group."""
+    return 2 * K + (d_in - K) * bits // 8 + 4 * (d_in - K) // GROUP
+
 
 def algorithmic_bytes():
     """Bytes the method itself must move per call: packed weights, rotation, x, y."""
-    per_row = 2 * K + (D - K) * BITS // 8 + 4 * (D - K) // GROUP
-    weights = per_row * N
+    weights = row_bytes(D, BITS) * N
     rot = 2 * 128 * 128 * HEADS
     xy = 2 * M * (D + N)
     return dict(weights=weights, rotation=rot, xy=xy, call=weights + rot + xy,
                 gemm_kernel=weights + 2 * M * D + 2 * M * N,
                 gemm_kernel_qkv=3 * weights + 2 * M * D + 3 * 2 * M * N)
+
+
+def pct(v, q):
+    return float(np.percentile(np.asarray(v, dtype=np.float64), q))
+
+
+class Timer:
+    """Captures `fn` into one hipGraph (unless eager) and times replays, each between its own events."""
+
+    def __init__(self, torch, stream, eager=False):
+        self.torch, self.stream, self.eager = torch, stream, eager
+
+    def prepare(self, fn):
+        torch = self.torch
+        with torch.cuda.stream(self.stream):
+            fn()                                   # eager once: first-use work happens outside the graph
+            self.stream.synchronize()
+            if self.eager:
+                return fn
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=self.stream):
+                fn()
+        return g.replay
+
+    def run(self, fn, steps, warmup):
+        """Returns dict(ms median / p10 / p90 per step from events, wall_ms mean per step)."""
+        torch = self.torch
+        run = self.prepare(fn)
+        with torch.cuda.stream(self.stream):
+            for _ in range(warmup):
+                run()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                  for _ in range(steps)]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for e0, e1 in ev:
+                e0.record(self.stream)
+                run()
+                e1.record(self.stream)
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+        ms = [e0.elapsed_time(e1) for e0, e1 in ev]
+        return {"median": pct(ms, 50), "p10": pct(ms, 10), "p90": pct(ms, 90), "wall": wall / steps * 1e3}
 
 
 def cpu_baseline(seconds_target=12.0):
@@ -100,38 +163,20 @@ SWEEP_SHAPES = [
     # not one of the benchmark's configs: a large streaming launch (7B-shaped vocabulary projection)
     ("vocab 4096->32000, no rotation, INT4", 4096, 32000, 4, "none", (1, 16, 64)),
 ]
+# the rows the default run carries in its JSON line: the M = 64 calls of the two MLP configs
+BOUNDED_SWEEP = ("7B gate/up", "7B down", "13B up", "13B down")
 
 
-def shape_sweep(args):
-    """One JSON line per (shape, M): us per call of the library against a fp16 torch.matmul, both
-    cycling over enough distinct copies of the weights to stay out of the last-level cache."""
-    import torch
+def shape_sweep(torch, shapes, ms_override, reps, emit):
+    """us per call of the library against a fp16 torch.matmul for each (shape, M), both cycling over
+    enough distinct copies of the weights to stay out of the last-level cache; 32 calls per hipGraph
+    replay, median over `reps` replays.  `emit` receives one dict per row."""
     from paper_2506_13472_amd import binding as B, synth, torch_glue as T
     dev = torch.device("cuda:0")
-    stream = torch.cuda.Stream()
+    timer = Timer(torch, torch.cuda.Stream())
     modes = {"headwise": B.Q_HEADWISE, "full": B.Q_FULL, "none": B.Q_NONE}
-
-    def time_graph(step, reps):
-        with torch.cuda.stream(stream):
-            step()
-            stream.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=stream):
-                step()
-            for _ in range(3):
-                g.replay()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            stream.synchronize()
-            e0.record(stream)
-            for _ in range(reps):
-                g.replay()
-            e1.record(stream)
-            stream.synchronize()
-        return e0.elapsed_time(e1) * 1e-3 / reps
-
-    for name, D_, N_, bits, mode, Ms in SWEEP_SHAPES:
-        if args.sweep_filter and args.sweep_filter not in name:
-            continue
+    calls = 32
+    for name, D_, N_, bits, mode, Ms in shapes:
         W = synth.make_weight(11, N_, D_)
         lam = synth.descending_spectrum(13, D_, D_ // 128 if mode == "headwise" else 1)
         Q = None
@@ -148,10 +193,8 @@ def shape_sweep(args):
         w16 = torch.from_numpy(W).to(dev)
         n16 = max(2, (320 << 20) // (2 * N_ * D_) + 1)
         W16 = [w16.clone() for _ in range(n16)]
-        per_row = 2 * K + (D_ - K) * bits // 8 + 4 * (D_ - K) // GROUP
         rot_bytes = {"headwise": 2 * 128 * D_, "full": 2 * D_ * D_, "none": 0}[mode]
-        calls = 32
-        for M_ in ([int(v) for v in args.sweep_m.split(",")] if args.sweep_m else Ms):
+        for M_ in (ms_override or Ms):
             x = torch.from_numpy(synth.make_activations(17, M_, D_)).to(dev)
             y = torch.empty((M_, N_), dtype=torch.float16, device=dev)
             ws = T.alloc_workspace(base, M_)
@@ -163,35 +206,39 @@ def shape_sweep(args):
             def step16():
                 for i in range(calls):
                     torch.matmul(x, W16[i % n16].t(), out=y)
-            us = time_graph(step, 20) / calls * 1e6
+            t_all = timer.run(step, reps, 3)
             B.rosaq_tune("stages", 2)
-            us_gemm = time_graph(step, 20) / calls * 1e6
+            t_gemm = timer.run(step, reps, 3)
             B.rosaq_tune("stages", 3)
-            us16 = time_graph(step16, 20) / calls * 1e6
-            nbytes = per_row * N_ + rot_bytes + 2 * M_ * (D_ + N_)
-            print(json.dumps({"shape": name, "D": D_, "N": N_, "M": M_, "bits": bits, "rotation": mode,
-                              "us_per_call": round(us, 2), "us_main_gemm": round(us_gemm, 2),
-                              "algorithmic_MB": round(nbytes / 1e6, 2),
-                              "GBps": round(nbytes / us / 1e3, 1),
-                              "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
-                              "tflops": round(2.0 * M_ * N_ * D_ / us / 1e6, 1),
-                              "fp16_matmul_us": round(us16, 2), "speedup_vs_fp16": round(us16 / us, 2),
-                              "distinct_copies": len(copies), "pack_s": round(t_pack, 2)}), flush=True)
+            t16 = timer.run(step16, reps, 3)
+            us = t_all["median"] * 1e3 / calls
+            us16 = t16["median"] * 1e3 / calls
+            nbytes = row_bytes(D_, bits) * N_ + rot_bytes + 2 * M_ * (D_ + N_)
+            emit({"shape": name, "D": D_, "N": N_, "M": M_, "bits": bits, "rotation": mode,
+                  "us_per_call": round(us, 2), "us_per_call_p10": round(t_all["p10"] * 1e3 / calls, 2),
+                  "us_per_call_p90": round(t_all["p90"] * 1e3 / calls, 2),
+                  "us_main_gemm": round(t_gemm["median"] * 1e3 / calls, 2),
+                  "algorithmic_MB": round(nbytes / 1e6, 2),
+                  "GBps": round(nbytes / us / 1e3, 1),
+                  "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                  "tflops": round(2.0 * M_ * N_ * D_ / us / 1e6, 1),
+                  "fp16_matmul_us": round(us16, 2), "speedup_vs_fp16": round(us16 / us, 2),
+                  "launch_shape_main_gemm": list(B.rosaq_launch_shape(M_, -(-N_ // 16) * 16, D_, bits)),
+                  "distinct_copies": len(copies), "pack_s": round(t_pack, 2)})
         for h in copies:
             h.free()
         del W16, w16
 
 
-def decode_workload(args):
+def decode_workload(torch, steps, warmup, absorbed=False):
     """The linears of a LLaMA-7B-shaped decode step at batch 64, INT4 g128, K = 128: per layer
     q/k/v (one batched call, shared head-wise rotation), o (head-wise), gate/up (one batched call
     sharing one dense 4096 x 4096 rotation) and down (no rotation, the paper's setting for W_D);
-    32 layers per step, every layer its own device copy of weights and rotations.  Prints one JSON
-    line with the time per step next to the same linears as fp16 torch.matmul calls."""
-    import torch
+    32 layers per step, every layer its own device copy of weights and rotations.  Returns a dict with
+    the time per step next to the same linears as fp16 torch.matmul calls."""
     from paper_2506_13472_amd import binding as B, synth, torch_glue as T
     dev = torch.device("cuda:0")
-    stream = torch.cuda.Stream()
+    timer = Timer(torch, torch.cuda.Stream())
     d, f, L = 4096, 11008, 32
     t0 = time.perf_counter()
     Qh_a, Qh_o = synth.random_orthogonal_blocks(21, d // 128), synth.random_orthogonal_blocks(22, d // 128)
@@ -199,7 +246,7 @@ def decode_workload(args):
     Qf, lam_f = synth.random_orthogonal_dense(24, d), synth.descending_spectrum(25, d, 1)
     lam_n = synth.descending_spectrum(26, f, 1)
     base = {}
-    ab = bool(args.absorbed)      # rotations folded into the producing layers offline (Sec. 3.1, App. G)
+    ab = bool(absorbed)      # rotations folded into the producing layers offline (weight-splitting appendix)
     for j, name in enumerate("qkv"):
         base[name] = B.rosaq_pack_weights(synth.make_weight(40 + j, d, d), Qh_a, lam_h, K, 4, B.Q_HEADWISE,
                                           rotation_absorbed=ab)
@@ -217,7 +264,9 @@ def decode_workload(args):
     xh = torch.from_numpy(synth.make_activations(8, M, f)).to(dev)
     y_d = [torch.empty((M, d), dtype=torch.float16, device=dev) for _ in range(4)]
     y_f = [torch.empty((M, f), dtype=torch.float16, device=dev) for _ in range(2)]
-    ws_bytes = max(B.rosaq_workspace_bytes(h, M) for h in base.values())
+    ws_bytes = max([B.rosaq_workspace_bytes(h, M) for h in base.values()] +
+                   [B.rosaq_workspace_bytes_batch([base[n] for n in "qkv"], M),
+                    B.rosaq_workspace_bytes_batch([base["gate"], base["up"]], M)])
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     qkv = [B.BatchArgs([lay[n] for n in "qkv"], [y.data_ptr() for y in y_d[:3]], [y.stride(0) for y in y_d[:3]])
            for lay in layers]
@@ -256,55 +305,46 @@ def decode_workload(args):
                 torch.matmul(x, W_gu[l][j * f:(j + 1) * f].t(), out=y_f[j])
             torch.matmul(xh, W_dn[l].t(), out=y_d[3])
 
-    def time_steps(fn, steps, warmup):
-        with torch.cuda.stream(stream):
-            fn()
-            stream.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=stream):
-                fn()
-            for _ in range(warmup):
-                g.replay()
-            stream.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(steps):
-                g.replay()
-            stream.synchronize()
-            return (time.perf_counter() - t0) / steps
-
-    steps = args.decode_steps
-    t = time_steps(step, steps, args.warmup)
+    t = timer.run(step, steps, warmup)
     B.rosaq_tune("stages", 2)
-    t_gemm = time_steps(step, steps, args.warmup)
+    t_gemm = timer.run(step, steps, warmup)
     B.rosaq_tune("stages", 3)
-    t16f = time_steps(step16_fused, steps, args.warmup)
-    t16s = time_steps(step16_separate, steps, args.warmup)
+    t16f = timer.run(step16_fused, steps, warmup)
+    t16s = timer.run(step16_separate, steps, warmup)
 
-    def row_bytes(D_):
-        return 2 * K + (D_ - K) * 4 // 8 + 4 * (D_ - K) // GROUP
-    per_layer = (4 * d * row_bytes(d) + 2 * f * row_bytes(d) + d * row_bytes(f)     # packed weights
+    per_layer = (4 * d * row_bytes(d, 4) + 2 * f * row_bytes(d, 4) + d * row_bytes(f, 4)   # packed weights
                  + (0 if ab else 2 * 2 * 128 * d + 2 * d * d)                       # two head-wise + one dense rotation
                  + 2 * M * (4 * d + 4 * d) + 2 * M * (d + 2 * f) + 2 * M * (f + d))  # x and y of the four calls
     fp16_layer = 2 * (4 * d * d + 3 * d * f) + 2 * M * (2 * d + 4 * d) + 2 * M * (d + 2 * f) + 2 * M * (f + d)
-    print(json.dumps({
+    ms = t["median"]
+    out = {
         "workload": "llama7b_decode_linears_M64_int4" + ("_rotations_absorbed" if ab else ""),
         "layers": L, "linears_per_step": 7 * L, "M": M,
         "calls_per_layer": ("rosaq_linear_batch(q,k,v) + rosaq_linear(o) + rosaq_linear_batch(gate,up) + "
                             "rosaq_linear(down): inputs arrive rotated, run time only permutes them") if ab else
                            ("rosaq_linear_batch(q,k,v; head-wise) + rosaq_linear_headwise(o) + "
                             "rosaq_linear_batch(gate,up; dense 4096^2 rotation) + rosaq_linear(down; no rotation)"),
-        "steps_timed": steps, "ms_per_step": round(t * 1e3, 4), "total_s": round(t * steps, 4),
-        "ms_per_step_main_gemms_only": round(t_gemm * 1e3, 4),
+        "steps_timed": steps, "ms_per_step": round(ms, 4), "ms_per_step_p10": round(t["p10"], 4),
+        "ms_per_step_p90": round(t["p90"], 4), "total_s": round(ms * steps * 1e-3, 4),
+        "tokens_per_s": round(M / (ms * 1e-3), 1),
+        "ms_per_step_main_gemms_only": round(t_gemm["median"], 4),
         "algorithmic_GB_per_step": round(per_layer * L / 1e9, 3),
-        "GBps": round(per_layer * L / t / 1e9, 1), "frac_of_hbm_peak": round(per_layer * L / t / 1e9 / HBM_PEAK_GBS, 4),
-        "packed_GB_resident": round(packed_bytes / 1e9, 3), "setup_s_one_layer_incl_synthetic_weights": round(t_pack, 1),
+        "GBps": round(per_layer * L / ms / 1e6, 1),
+        "frac_of_hbm_peak": round(per_layer * L / ms / 1e6 / HBM_PEAK_GBS, 4),
+        "packed_GB_resident": round(packed_bytes / 1e9, 3),
+        "setup_s_one_layer_incl_synthetic_weights": round(t_pack, 1),
         "fp16": {"impl": "torch.matmul fp16 (vendor GEMM), one hipGraph per step",
-                 "ms_per_step_4_gemms_per_layer_fused_qkv_gateup": round(t16f * 1e3, 4),
-                 "ms_per_step_7_gemms_per_layer": round(t16s * 1e3, 4),
+                 "ms_per_step_4_gemms_per_layer_fused_qkv_gateup": round(t16f["median"], 4),
+                 "ms_per_step_7_gemms_per_layer": round(t16s["median"], 4),
                  "GB_per_step": round(fp16_layer * L / 1e9, 3),
-                 "GBps_fused": round(fp16_layer * L / t16f / 1e9, 1)},
-        "speedup_vs_fp16_fused": round(t16f / t, 3), "speedup_vs_fp16_separate": round(t16s / t, 3),
-        "data": "synthetic"}), flush=True)
+                 "GBps_fused": round(fp16_layer * L / t16f["median"] / 1e6, 1)},
+        "speedup_vs_fp16_fused": round(t16f["median"] / ms, 3),
+        "speedup_vs_fp16_separate": round(t16s["median"] / ms, 3),
+        "data": "synthetic"}
+    for lay in layers:
+        for h in lay.values():
+            h.free()
+    return out
 
 
 def main():
@@ -320,6 +360,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16", action="store_true", help="skip the fp16 GEMM comparison")
     ap.add_argument("--no-probe", action="store_true", help="skip the pure read-stream ceiling")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the bounded MLP sweep of the default line")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode step of the default line")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the bench, time every MLP / attention shape of the task's configs "
                          "(one JSON line each)")
@@ -339,6 +381,7 @@ def main():
     ap.add_argument("--nt", type=int, default=0, help="tuning aid: 16-channel tiles per workgroup")
     ap.add_argument("--wpb", type=int, default=0, help="tuning aid: waves per workgroup (8 or 16)")
     ap.add_argument("--depth", type=int, default=0, help="tuning aid: units in flight per wave (2-4)")
+    ap.add_argument("--splits", type=int, default=0, help="tuning aid: workgroups per output tile (1-16)")
     ap.add_argument("--rot", default="", help="tuning aid: mt,nt,depth of the dense-rotation launch")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -361,21 +404,23 @@ def main():
         print(json.dumps({"copy_calibration_bytes_read": n, "bytes_written": n, "copies": 20}))
         return
     B.lib()
-    for key in ("mt", "nt", "wpb", "depth"):
+    for key in ("mt", "nt", "wpb", "depth", "splits"):
         B.rosaq_tune(key, getattr(args, key))
     if args.rot:
         for key, v in zip(("rot_mt", "rot_nt", "rot_depth"), args.rot.split(",")):
             B.rosaq_tune(key, int(v))
     if args.sweep:
-        shape_sweep(args)
+        shapes = [s for s in SWEEP_SHAPES if not args.sweep_filter or args.sweep_filter in s[0]]
+        ms = [int(v) for v in args.sweep_m.split(",")] if args.sweep_m else None
+        shape_sweep(torch, shapes, ms, 20, lambda row: print(json.dumps(row), flush=True))
         return
     if args.decode:
-        decode_workload(args)
+        print(json.dumps(decode_workload(torch, args.decode_steps, args.warmup, args.absorbed)), flush=True)
         return
 
     # ---- synthetic layers: calibrate (PCA per head on the GPU), pack, all through the C ABI ------
     # q, k, v read the same activations, hence share one PCA; o has its own input and PCA.
-    t_pack_only = 0.0
+    t_pack = 0.0
     t_pca = 0.0
     handles = []
     rot_first = None
@@ -393,14 +438,13 @@ def main():
             Qb, lam = rot[0] if j < 3 else rot[1]
             t0 = time.perf_counter()
             handles.append(B.rosaq_pack_weights(W, Qb, lam, K, BITS, B.Q_HEADWISE))
-            t_pack_only += time.perf_counter() - t0
-    t_pack = t_pack_only
+            t_pack += time.perf_counter() - t0
     packed_bytes = sum(h.device_bytes for h in handles)
     x = torch.from_numpy(synth.make_activations(7, M, D)).to(dev)
     ys = [torch.empty((M, N), dtype=torch.float16, device=dev) for _ in range(4)]
-    ws = T.alloc_workspace(handles[0], M)
+    ws = torch.empty(B.rosaq_workspace_bytes_batch(handles[:3], M), dtype=torch.uint8, device=dev)
 
-    stream = torch.cuda.Stream()
+    timer = Timer(torch, torch.cuda.Stream(), eager=args.no_graph)
     calls = [(handles[i % len(handles)], ys[i % 4]) for i in range(CALLS_PER_STEP)]
     n_layers = CALLS_PER_STEP // 4
     qkv = [B.BatchArgs([handles[(4 * l + j) % len(handles)] for j in range(3)],
@@ -420,61 +464,40 @@ def main():
             if args.only != "qkv":
                 T.linear(wo[l], x, ys[3], ws)
 
-    def make_runner():
-        if args.no_graph:
-            return issue_step
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=stream):
-            issue_step()
-        return g.replay
-
-    def timed(run, steps, warmup):
-        with torch.cuda.stream(stream):
-            for _ in range(warmup):
-                run()
-            stream.synchronize()
-            e0 = torch.cuda.Event(enable_timing=True)
-            e1 = torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            e0.record(stream)
-            for _ in range(steps):
-                run()
-            e1.record(stream)
-            torch.cuda.synchronize()
-            wall = time.perf_counter() - t0
-        return wall, e0.elapsed_time(e1) * 1e-3
-
-    with torch.cuda.stream(stream):
-        issue_step()                      # eager once: sizes the workspace path, fills xhat
-        stream.synchronize()
-        run = make_runner()
-    wall, ev = timed(run, args.steps, args.warmup)
-
+    t_step = timer.run(issue_step, args.steps, args.warmup)
     # dominant kernel alone (main GEMM; xhat fragments left in the workspace by the runs above)
     B.rosaq_tune("stages", 2)
-    with torch.cuda.stream(stream):
-        run_gemm = make_runner()
-    _, ev_gemm = timed(run_gemm, args.steps, args.warmup)
+    t_gemm = timer.run(issue_step, args.steps, args.warmup)
     B.rosaq_tune("stages", 1)
-    with torch.cuda.stream(stream):
-        run_rot = make_runner()
-    _, ev_rot = timed(run_rot, args.steps, args.warmup)
+    t_rot = timer.run(issue_step, args.steps, args.warmup)
     B.rosaq_tune("stages", 3)
 
     ab = algorithmic_bytes()
-    n_calls = args.steps * CALLS_PER_STEP
-    us_call = wall / n_calls * 1e6
-    gbs = ab["call"] * n_calls / wall / 1e9
+    calls_per_step = CALLS_PER_STEP if not args.only else CALLS_PER_STEP // 4 * (3 if args.only == "qkv" else 1)
+    us_call = t_step["median"] * 1e3 / calls_per_step
+    gbs = ab["call"] * calls_per_step / (t_step["median"] * 1e-3) / 1e9
     # per launch of the dominant kernel: unbatched, every launch is one linear; batched, a
     # layer issues one q/k/v launch and one o launch (the mean launch moves half of both)
-    launches = n_calls if args.unbatched else n_calls // 2
-    gemm_bytes = ab["gemm_kernel"] if args.unbatched else (ab["gemm_kernel_qkv"] + ab["gemm_kernel"]) // 2
-    if args.only:
-        launches = n_calls // 4
-        gemm_bytes = ab["gemm_kernel_qkv"] if args.only == "qkv" else ab["gemm_kernel"]
-    us_gemm = ev_gemm / launches * 1e6
+    shape_one = tuple(B.rosaq_launch_shape(M, N, D, BITS))
+    shape_qkv = tuple(B.rosaq_launch_shape(M, 3 * N, D, BITS))
+    launch_kinds = {"o": [(1, shape_one, ab["gemm_kernel"])], "qkv": [(3, shape_qkv, ab["gemm_kernel_qkv"])]}
+    if args.unbatched:
+        kinds, launches = launch_kinds["o"], CALLS_PER_STEP
+    elif args.only:
+        kinds, launches = launch_kinds[args.only], n_layers
+    else:
+        kinds, launches = launch_kinds["qkv"] + launch_kinds["o"], 2 * n_layers
+    gemm_bytes = sum(k[2] for k in kinds) // len(kinds)
+    us_gemm = t_gemm["median"] * 1e3 / launches
     gemm_gbs = gemm_bytes / (us_gemm * 1e-6) / 1e9
+    measured = [MEASURED_TRAFFIC_KIB.get((k[0],) + k[1]) for k in kinds]
+    if all(m is not None for m in measured):
+        traffic = sum((m[0] + m[1]) * 1024 for m in measured) // len(measured)
+        traffic_note = "rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE, mean over the launch kinds of a step"
+    else:
+        traffic = None
+        traffic_note = ("no rocprofv3 measurement on file for launch shape(s) " +
+                        ", ".join(str((k[0],) + k[1]) for k, m in zip(kinds, measured) if m is None))
 
     # ---- fp16 dense GEMM on the same shape, same cold-weight protocol ----------------
     fp16 = None
@@ -486,18 +509,7 @@ def main():
         def fp16_step():
             for i in range(CALLS_PER_STEP):
                 torch.matmul(x, Ws[i % n_w].t(), out=yb)
-        with torch.cuda.stream(stream):
-            fp16_step()
-            stream.synchronize()
-            if args.no_graph:
-                run16 = fp16_step
-            else:
-                g16 = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g16, stream=stream):
-                    fp16_step()
-                run16 = g16.replay
-        w16, _ = timed(run16, args.steps, args.warmup)
-        us16 = w16 / n_calls * 1e6
+        us16 = timer.run(fp16_step, args.steps, args.warmup)["median"] * 1e3 / CALLS_PER_STEP
         fp16 = {"us_per_call": round(us16, 3),
                 "GBps": round((2 * N * D + ab["xy"]) / (us16 * 1e-6) / 1e9, 1),
                 "rosaq_speedup": round(us16 / us_call, 3), "impl": "torch.matmul fp16 (vendor GEMM)"}
@@ -511,18 +523,8 @@ def main():
         def own16_step():
             for i in range(CALLS_PER_STEP):
                 T.linear(h16[i % n_w], x, yb, ws)
-        with torch.cuda.stream(stream):
-            own16_step()
-            stream.synchronize()
-            if args.no_graph:
-                run_own = own16_step
-            else:
-                g_own = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g_own, stream=stream):
-                    own16_step()
-                run_own = g_own.replay
-        w_own, _ = timed(run_own, args.steps, args.warmup)
-        fp16["own_all_salient_us_per_call"] = round(w_own / n_calls * 1e6, 3)
+        fp16["own_all_salient_us_per_call"] = round(
+            timer.run(own16_step, args.steps, args.warmup)["median"] * 1e3 / CALLS_PER_STEP, 3)
         for h in h16:
             h.free()
 
@@ -541,60 +543,60 @@ def main():
                 for i in range(CALLS_PER_STEP):
                     B.rosaq_stream_probe(srcs[i % n_src].data_ptr(), pb, shared.data_ptr(), shared.numel(),
                                          per_wg, 256, 512, sink.data_ptr(), sink.numel(), sp)
-            with torch.cuda.stream(stream):
-                probe_step()
-                stream.synchronize()
-                if args.no_graph:
-                    runp = probe_step
-                else:
-                    gp = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(gp, stream=stream):
-                        probe_step()
-                    runp = gp.replay
-            _, evp = timed(runp, args.steps, args.warmup)
-            probe[name] = round(evp / n_calls * 1e6, 3)
+            probe[name] = round(timer.run(probe_step, args.steps, args.warmup)["median"] * 1e3 / CALLS_PER_STEP, 3)
         probe["weights_only_GBps"] = round(pb / (probe["weights_only_us"] * 1e-6) / 1e9, 1)
         del srcs
-
-    # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE (x 2.0 by a 256 MiB copy)
-    # + WRITE_SIZE (x 1.0), profiles/gemm_kernel_llama7b_attn_M64_int4.md: one 4096 x 4096 launch moves
-    # 13.97 MB + 0.52 MB, a q/k/v launch 33.39 MB + 1.57 MB; the default step averages the two.
-    one, qkv3 = 13640 * 1024 + 512 * 1024, 32612 * 1024 + 1536 * 1024
-    traffic = {None: (one + qkv3) // 2, "qkv": qkv3, "o": one}[args.only] if not args.unbatched else one
 
     out = {
         "metric": "fused ROSAQ linear HBM GB/s at M=64 (algorithmic bytes / time)",
         "value": round(gbs, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(wall / args.steps * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(t_step["wall"], 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16 x int4 -> f32 accumulate", "data": "synthetic",
         "config": {"workload": "llama7b_attn_qkvo_M64_int4_headwise", "D": D, "N": N, "M": M, "K": K,
-                   "bits": BITS, "group": GROUP, "heads": HEADS, "calls_per_step": CALLS_PER_STEP,
+                   "bits": BITS, "group": GROUP, "heads": HEADS, "calls_per_step": calls_per_step,
                    "distinct_packed_weights": len(handles), "packed_MB": round(packed_bytes / 1e6, 1),
                    "launch": "eager" if args.no_graph else "hipGraph per step",
                    "calls": "4 x rosaq_linear_headwise per layer" if args.unbatched else
                             "rosaq_linear_batch(q,k,v) + rosaq_linear_headwise(o) per layer",
-                   "tiles": {k: getattr(args, k) or "heuristic" for k in ("mt", "nt", "wpb", "depth")},
-                   "launch_shape_mt_nt_waves_depth": {"one_layer": list(B.rosaq_launch_shape(M, N, D, BITS)),
-                                                       "qkv": list(B.rosaq_launch_shape(M, 3 * N, D, BITS))}},
+                   "tiles": {k: getattr(args, k) or "heuristic" for k in ("mt", "nt", "wpb", "depth", "splits")},
+                   "launch_shape_mt_nt_waves_depth_splits": {"one_layer": list(shape_one), "qkv": list(shape_qkv)}},
+        "timing": "each step between its own pair of HIP events on the launch stream; value, us_per_linear and "
+                  "frac_of_hbm_peak use the median step; ms_per_step is host wall time over all steps / steps",
+        "step_ms": {"median": round(t_step["median"], 5), "p10": round(t_step["p10"], 5),
+                    "p90": round(t_step["p90"], 5)},
         "us_per_linear": round(us_call, 3),
         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         "tflops": round(2.0 * M * N * (D + 128) / (us_call * 1e-6) / 1e12, 2),
-        "event_ms_per_step": round(ev / args.steps * 1e3, 5),
-        "rotation_kernel_us": round(ev_rot / launches * 1e6, 3),
+        "rotation_kernel_us": round(t_rot["median"] * 1e3 / launches, 3),
         "pack_seconds_per_layer": round(t_pack / len(handles), 3),
         "pca_seconds_per_rotation": round(t_pca / (2 * args.layers), 4),
         "fp16_gemm": fp16,
         "stream_probe": probe,
         "roofline": {"kernel": "gemm_kernel", "bound": "hbm", "achieved": round(gemm_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": traffic, "bytes_per_launch": gemm_bytes, "launches_per_step": launches // args.steps,
-                     "us_per_launch": round(us_gemm, 3)},
+                     "traffic": traffic, "traffic_note": traffic_note, "bytes_per_launch": gemm_bytes,
+                     "launches_per_step": launches, "us_per_launch": round(us_gemm, 3),
+                     "us_per_launch_p10": round(t_gemm["p10"] * 1e3 / launches, 3),
+                     "us_per_launch_p90": round(t_gemm["p90"] * 1e3 / launches, 3)},
     }
+    for h in handles:
+        h.free()
+    del handles, qkv, wo, calls
+    torch.cuda.empty_cache()
+    if not args.no_sweep:
+        rows = []
+        shapes = [s for s in SWEEP_SHAPES if s[0].startswith(BOUNDED_SWEEP)]
+        shape_sweep(torch, shapes, [64], 10, rows.append)
+        out["sweep"] = {"what": "single calls at M = 64 of the INT3 7B MLP and the INT4 13B MLP shapes, K = 128, "
+                                "median of 10 replays of 32 calls over distinct weight copies (cold HBM)",
+                        "rows": rows}
+        torch.cuda.empty_cache()
+    if not args.no_decode:
+        out["decode"] = decode_workload(torch, args.decode_steps, args.warmup)
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
-    for h in handles:
-        h.free()
 
 
 if __name__ == "__main__":

@@ -582,9 +582,9 @@ __global__ __launch_bounds__(256) void gather_kernel(const _Float16* __restrict_
                                                      int M, int KS, const int32_t* __restrict__ perm,
                                                      uint4* __restrict__ xf, int total,
                                                      unsigned* __restrict__ zero_ptr, int zero_count) {
-  if (blockIdx.x == 0)   // tickets of the GEMM launches that follow in this call
-    for (int i = threadIdx.x; i < zero_count; i += 256) zero_ptr[i] = 0u;
   const int idx = blockIdx.x * 256 + threadIdx.x;
+  // tickets of the GEMM launches that follow in this call, spread over the launch's threads
+  for (int i = idx; i < zero_count; i += gridDim.x * 256) zero_ptr[i] = 0u;
   if (idx >= total) return;
   const int lane = idx & 63, mt = (idx >> 6) & 3;
   const int ks = (idx >> 8) % KS, mb = (idx >> 8) / KS;
@@ -635,8 +635,10 @@ __global__ __launch_bounds__(256) void rotate_headwise_kernel(
     const _Float16* __restrict__ x, int64_t ldx, int M, int KS, int H, const uint4* __restrict__ qh,
     const int32_t* __restrict__ pos, _Float16* __restrict__ xf, unsigned* __restrict__ zero_ptr,
     int zero_count) {
-  if (blockIdx.x == 0 && blockIdx.y == 0)   // tickets of the GEMM launch that follows in this call
-    for (int i = threadIdx.x; i < zero_count; i += 256) zero_ptr[i] = 0u;
+  // tickets of the GEMM launch that follows in this call, spread over the launch's threads
+  for (int i = (blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x; i < zero_count;
+       i += gridDim.x * gridDim.y * 256)
+    zero_ptr[i] = 0u;
   const int lane = threadIdx.x & 63;
   const int mt = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // the eight column tiles of a head share x_h: keep them on one XCD (id % 8)
