@@ -194,3 +194,23 @@ def test_top_rule_beats_the_ablation_rules_on_output_error():
     assert abs(err["both_as_in_the_paper"] - err["top"]) < 0.25 * err["top"]
     # with the fp16 budget held at K (K/2 + K/2) the bottom half is wasted: worse than Top
     assert err["top"] < err["both_same_budget"] < err["bottom"]
+
+
+def test_headwise_pca_beats_global_pca_when_calibration_rows_are_scarce():
+    # synthetic analogue of the head-wise ablation appendix (one PCA per head, Eq. 6, against one
+    # PCA over the concatenated heads, Eq. 8): with D / 2 calibration rows the per-head rotation
+    # gives the smaller output error on held-out activations, for every seed
+    from oracle import ablation_table as A
+    for seed in (0, 1, 2):
+        r = A.headwise_ablation(seed, n_cal=256)
+        assert r["head-wise PCA, K/H per head"] < r["global PCA"]
+        assert r["head-wise PCA, top-K over all heads"] < r["global PCA"]
+        assert r["global PCA"] < 0.5 * r["no rotation (top-K by magnitude)"]
+
+
+def test_ablation_table_selection_rows_order_like_the_paper():
+    from oracle import ablation_table as A
+    r = A.selection_ablation(0, D=384, N=48, n_cal=512, M=64, starts=3)
+    assert r["Top"] < 0.6 * r["Random"] and r["Top"] < 0.6 * r["Bottom"]
+    assert abs(r["Top & Bottom"] - r["Top"]) < 0.25 * r["Top"]
+    assert r["Bottom"] <= r["none (all low-bit)"] * 1.05
