@@ -89,8 +89,7 @@ typedef struct {
 } rosaq_pack_desc;
 
 /* rosaq_pack_weights - offline step of the method (Sec. 3.1-3.3, Eq. 1-3):
- *   1. What = W Q in fp64, rounded once to fp16 (HEADWISE: per 128-column block; large layers
- *      run this product on the GPU, with the same result);
+ *   1. What = W Q in fp64, rounded once to fp16 (HEADWISE: per 128-column block);
  *   2. salient_idx = the K channels picked by select_rule (default: largest eigenvalues), ascending;
  *      storage order perm = [salient_idx ; all other channels ascending];
  *   3. W_S = What[:, salient_idx] kept as fp16;
@@ -99,8 +98,9 @@ typedef struct {
  *      z = clamp(rne(-min/s), 0, 2^bits-1), q = clamp(rne(w/s)+z, 0, 2^bits-1)
  *      (fp64 arithmetic, round-half-to-even; the paper fixes only "per-group,
  *      128 channels, INT3/INT4": this formula is this library's reading);
- *   5. unless host_only, device copies in the kernels' fragment order (plus an
- *      fp16 copy of Q) are uploaded on `hip_stream` and the call waits for them.
+ *   5. unless host_only, steps 1, 3 and 4 run on the GPU (W and Q are uploaded on `hip_stream`;
+ *      the results are bit-identical to the host path) and leave the layer in device memory in
+ *      the kernels' fragment order, plus an fp16 copy of Q; the call waits for them.
  * hip_stream is a hipStream_t (NULL = default stream).  *out is owned by the
  * library until rosaq_free.  Errors: NULL, SHAPE, ARG, NONFINITE, NOMEM, HIP. */
 int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_packed_t** out);
@@ -243,12 +243,14 @@ int rosaq_tune(const char* key, int32_t value);
 int rosaq_launch_shape(int32_t M, int32_t channels, int32_t in_features, int32_t bits, int32_t* shape_out);
 
 /* Testing aid, host only: the weight image exactly as the kernels read it, rebuilt from the handle's
- * canonical arrays.  which = 0: fp16 salient fragments [tiles][K/32][64 lanes][8 halves]; which = 1:
+ * canonical arrays (which = 2 / 3: the same two images copied back from the device buffers the kernels
+ * read; needs a handle packed without host_only).  which = 0: fp16 salient fragments [tiles][K/32][64 lanes][8 halves]; which = 1:
  * low-bit records [tiles][G] of 1088 bytes (INT4: [64 lanes][4 dwords] codes, then 16 dwords
  * scale | zero << 16) or 832 bytes (INT3: [64 lanes][3 dwords]); tiles = 8 * ceil(N / 128).
  * Lane l of tile t holds output channel 16 t + l % 16 and, per 32-channel k-step, the 8 storage-order
  * channels 8 (l / 16) .. + 7.  out_host may be NULL to query the size; *bytes is capacity in, size out.
- * Errors: ROSAQ_ERR_NULL, ROSAQ_ERR_ARG, ROSAQ_ERR_WORKSPACE (buffer too small; *bytes set to the need). */
+ * Errors: ROSAQ_ERR_NULL, ROSAQ_ERR_ARG, ROSAQ_ERR_WORKSPACE (buffer too small; *bytes set to the need),
+ * ROSAQ_ERR_HOSTONLY, ROSAQ_ERR_HIP (which = 2 / 3). */
 int rosaq_packed_image(const rosaq_packed_t* p, int32_t which, void* out_host, size_t* bytes);
 
 /* Testing aid, host only: the main GEMM's map from workgroup index to (channel chunk, row group) for a

@@ -104,74 +104,92 @@ static int check_desc(const rosaq_pack_desc* d) {
     }                                                                           \
   } while (0)
 
-// What = fp16(W Q) on the GPU (fp64 FMA chain per output), dense or block-diagonal Q: the
-// host version of the dense product takes tens of seconds at D >= 4096, of the head-wise one
-// a few tenths of a second per 4096 x 4096 layer.
-static int rotate_on_device(const rosaq_pack_desc& d, hipStream_t st, std::vector<uint16_t>* out) {
-  const size_t N = d.out_features, D = d.in_features;
-  void *dW = nullptr, *dQ = nullptr, *dO = nullptr;
-  std::vector<uint16_t> wc;
-  const uint16_t* wsrc = d.W;
-  if (d.ldw != static_cast<int64_t>(D)) {
-    wc.resize(N * D);
-    for (size_t n = 0; n < N; ++n) std::memcpy(&wc[n * D], d.W + n * d.ldw, D * 2);
-    wsrc = wc.data();
-  }
-  out->resize(N * D);
-  hipError_t e = hipMalloc(&dW, N * D * 2);
-  const bool headwise = d.q_mode == ROSAQ_Q_HEADWISE;
-  const size_t q_bytes = (headwise ? D * kHeadDim : D * D) * 4;
-  if (e == hipSuccess) e = hipMalloc(&dQ, q_bytes);
-  if (e == hipSuccess) e = hipMalloc(&dO, N * D * 2);
-  if (e == hipSuccess) e = hipMemcpyAsync(dW, wsrc, N * D * 2, hipMemcpyHostToDevice, st);
-  if (e == hipSuccess) e = hipMemcpyAsync(dQ, d.Q, q_bytes, hipMemcpyHostToDevice, st);
-  int rc = ROSAQ_OK;
-  if (e == hipSuccess) rc = launch_rotate_weights_f64(dW, dQ, dO, static_cast<int>(N), static_cast<int>(D), headwise ? 1 : 0, st);
-  if (e == hipSuccess && rc == ROSAQ_OK)
-    e = hipMemcpyAsync(out->data(), dO, N * D * 2, hipMemcpyDeviceToHost, st);
-  if (e == hipSuccess && rc == ROSAQ_OK) e = hipStreamSynchronize(st);
-  if (dW) (void)hipFree(dW);
-  if (dQ) (void)hipFree(dQ);
-  if (dO) (void)hipFree(dO);
-  if (rc != ROSAQ_OK) return rc;
-  if (e != hipSuccess) {
-    set_error(std::string("device rotation: ") + hipGetErrorString(e));
-    return ROSAQ_ERR_HIP;
-  }
-  return ROSAQ_OK;
-}
+// The offline step with the layer on the GPU: upload W (and Q), rotate in fp64 (Eq. 1), then one
+// pass from the rotated fp16 weight to the fragment images the kernels read and to the canonical
+// arrays (Sec. 3.2-3.3, Eq. 3), which come back to the host for rosaq_packed_export.  Only the
+// input checks and the ranking of D eigenvalues stay on the host.
+static int pack_device(const rosaq_pack_desc& d, hipStream_t st, rosaq_packed* p) {
+  std::string err;
+  int rc = pack_validate(d, &err);
+  if (rc != ROSAQ_OK) return fail(rc, err);
+  pack_select(d, &p->c);
+  Canonical& c = p->c;
+  const size_t N = c.N, D = c.D, K = c.K, C = D - K, G = c.G;
+  const size_t ntiles = (N + 127) / 128 * 8, ks_s = K / kKStep;
+  const bool rotate = d.q_mode != ROSAQ_Q_NONE, headwise = d.q_mode == ROSAQ_Q_HEADWISE;
+  const bool keep_q = rotate && !d.rotation_absorbed;
+  const size_t rec_dwords = (c.bits == 4 ? 256 : 192) + 16;
+  const size_t wS_bytes = ntiles * ks_s * 64 * 16, wq_bytes = ntiles * G * rec_dwords * 4;
+  const size_t qf_bytes = !keep_q ? 0 : (headwise ? (D / kHeadDim) * 8 * 4 * 64 * 16
+                                                  : (D / kTileN) * (D / kKStep) * 64 * 16);
+  const size_t q_bytes = !rotate ? 0 : (headwise ? D * kHeadDim : D * D) * sizeof(float);
 
-static int upload(rosaq_packed* p, const float* Q, hipStream_t st) {
-  DeviceImage img;
-  try {
-    build_device_image(p->c, Q, &img);
-  } catch (const std::exception&) { return fail(ROSAQ_ERR_NOMEM, "out of host memory"); }
-  const Canonical& c = p->c;
-  struct Part { const void* src; size_t bytes; void** dst; };
-  void* d_perm = nullptr;
-  void* d_pos = nullptr;
-  Part parts[] = {
-      {img.wS.data(), img.wS.size() * 4, &p->d_wS},
-      {img.wq.data(), img.wq.size() * 4, &p->d_wq},
-      {img.qf.data(), img.qf.size() * 4, &p->d_qf},
-      {c.perm.data(), c.perm.size() * 4, &d_perm},
-      {c.pos.data(), c.pos.size() * 4, &d_pos},
-  };
+  // the handle's device buffer: [wS | wq | qf | perm | pos]
+  struct Part { size_t bytes; void** dst; };
+  void *d_perm = nullptr, *d_pos = nullptr;
+  Part parts[] = {{wS_bytes, &p->d_wS}, {wq_bytes, &p->d_wq}, {qf_bytes, &p->d_qf},
+                  {D * 4, &d_perm}, {D * 4, &d_pos}};
   size_t total = 0;
   for (const Part& q : parts) total += align_up(std::max<size_t>(q.bytes, 16), 256);
   ROSAQ_HIP(hipGetDevice(&p->device));
-  ROSAQ_HIP(hipMalloc(&p->d_blob, total));
+  ROSAQ_HIP(hipMalloc(&p->d_blob, total));       // owned by the handle from here on (rosaq_free)
   p->blob_bytes = total;
+  p->host_only = false;
   size_t off = 0;
   for (const Part& q : parts) {
     *q.dst = static_cast<char*>(p->d_blob) + off;
-    if (q.src && q.bytes) ROSAQ_HIP(hipMemcpyAsync(*q.dst, q.src, q.bytes, hipMemcpyHostToDevice, st));
     off += align_up(std::max<size_t>(q.bytes, 16), 256);
   }
-  ROSAQ_HIP(hipStreamSynchronize(st));   // staging vectors die with this frame
   p->d_perm = static_cast<int32_t*>(d_perm);
   p->d_pos = static_cast<int32_t*>(d_pos);
-  p->host_only = false;
+
+  // scratch of this call: [W | What | Q | W_S | codes | scales | zeros | flag]
+  const size_t sizes[] = {N * D * 2, rotate ? N * D * 2 : 0, q_bytes, N * K * 2, N * C, N * G * 2, N * G * 2, 256};
+  size_t offs[8], tmp_total = 0;
+  for (int i = 0; i < 8; ++i) { offs[i] = tmp_total; tmp_total += align_up(std::max<size_t>(sizes[i], 16), 256); }
+  char* tmp = nullptr;
+  ROSAQ_HIP(hipMalloc(reinterpret_cast<void**>(&tmp), tmp_total));
+  unsigned flag = 0;
+  hipError_t e = hipMemcpy2DAsync(tmp + offs[0], D * 2, d.W, static_cast<size_t>(d.ldw) * 2, D * 2, N,
+                                  hipMemcpyHostToDevice, st);
+  if (e == hipSuccess && rotate) e = hipMemcpyAsync(tmp + offs[2], d.Q, q_bytes, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess) e = hipMemcpyAsync(d_perm, c.perm.data(), D * 4, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess) e = hipMemcpyAsync(d_pos, c.pos.data(), D * 4, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess) e = hipMemsetAsync(tmp + offs[7], 0, 256, st);
+  rc = ROSAQ_OK;
+  const char* what = tmp + offs[0];
+  if (e == hipSuccess && rotate) {
+    rc = launch_rotate_weights_f64(tmp + offs[0], tmp + offs[2], tmp + offs[1], static_cast<int>(N),
+                                   static_cast<int>(D), headwise ? 1 : 0, st);
+    what = tmp + offs[1];
+  }
+  if (e == hipSuccess && rc == ROSAQ_OK) {
+    QuantPackArgs a{};
+    a.what16 = what; a.N = c.N; a.D = c.D; a.K = c.K; a.bits = c.bits; a.perm = p->d_perm;
+    a.wS_image = p->d_wS; a.wq_image = p->d_wq;
+    a.W_S = tmp + offs[3]; a.codes = tmp + offs[4]; a.scales = tmp + offs[5]; a.zeros = tmp + offs[6];
+    a.flag = tmp + offs[7];
+    rc = launch_quantize_pack(a, st);
+  }
+  if (e == hipSuccess && rc == ROSAQ_OK && keep_q)
+    rc = launch_rotation_image(tmp + offs[2], c.D, headwise ? 1 : 0, p->d_perm, p->d_qf, st);
+  if (e == hipSuccess && rc == ROSAQ_OK) {
+    c.W_S.resize(N * K); c.codes.resize(N * C); c.scales.resize(N * G); c.zeros.resize(N * G);
+    if (N * K) e = hipMemcpyAsync(c.W_S.data(), tmp + offs[3], N * K * 2, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess && N * C) e = hipMemcpyAsync(c.codes.data(), tmp + offs[4], N * C, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess && N * G) e = hipMemcpyAsync(c.scales.data(), tmp + offs[5], N * G * 2, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess && N * G) e = hipMemcpyAsync(c.zeros.data(), tmp + offs[6], N * G * 2, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(&flag, tmp + offs[7], 4, hipMemcpyDeviceToHost, st);
+  }
+  const hipError_t es = hipStreamSynchronize(st);   // also before the scratch is freed
+  if (e == hipSuccess) e = es;
+  (void)hipFree(tmp);
+  if (rc != ROSAQ_OK) return rc;
+  if (e != hipSuccess) {
+    set_error(std::string("offline step on the device: ") + hipGetErrorString(e));
+    return ROSAQ_ERR_HIP;
+  }
+  if (flag) return fail(ROSAQ_ERR_NONFINITE, "rotated weight overflows fp16");
   return ROSAQ_OK;
 }
 
@@ -292,21 +310,14 @@ int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_pack
   if (!p) return fail(ROSAQ_ERR_NOMEM, "out of host memory");
   std::string err;
   try {
-    std::vector<uint16_t> rotated;
-    // small layers stay on the host (the transfer costs more than the product)
-    const bool on_device =
-        !desc->host_only &&
-        ((desc->q_mode == ROSAQ_Q_FULL && desc->in_features >= 1024) ||
-         (desc->q_mode == ROSAQ_Q_HEADWISE &&
-          static_cast<int64_t>(desc->out_features) * desc->in_features >= (1 << 20)));
-    if (on_device) {
-      // the packer validates Q and W before it uses the rotated matrix
-      rc = rotate_on_device(*desc, static_cast<hipStream_t>(hip_stream), &rotated);
-      if (rc != ROSAQ_OK) { delete p; return rc; }
+    if (desc->host_only) {
+      rc = pack_host(*desc, &p->c, &err);
+      if (rc != ROSAQ_OK) set_error(err);
+    } else {
+      rc = pack_device(*desc, static_cast<hipStream_t>(hip_stream), p);
     }
-    rc = pack_host(*desc, &p->c, &err, on_device ? &rotated : nullptr);
-  } catch (const std::exception&) { rc = ROSAQ_ERR_NOMEM; err = "out of host memory"; }
-  if (rc != ROSAQ_OK) { delete p; return fail(rc, err); }
+  } catch (const std::exception&) { rc = fail(ROSAQ_ERR_NOMEM, "out of host memory"); }
+  if (rc != ROSAQ_OK) { rosaq_free(p); return rc; }
   {
     uint64_t h = fnv1a(1469598103934665603ull, &desc->q_mode, sizeof(desc->q_mode));
     h = fnv1a(h, p->c.perm.data(), p->c.perm.size() * sizeof(int32_t));
@@ -317,10 +328,6 @@ int rosaq_pack_weights(const rosaq_pack_desc* desc, void* hip_stream, rosaq_pack
     p->rot_fingerprint = h;
   }
   if (desc->rotation_absorbed) p->c.q_mode = ROSAQ_Q_NONE;   // run time sees rotated activations
-  if (!desc->host_only) {
-    rc = upload(p, desc->Q, static_cast<hipStream_t>(hip_stream));
-    if (rc != ROSAQ_OK) { rosaq_free(p); return rc; }
-  }
   *out = p;
   return ROSAQ_OK;
 }
@@ -551,7 +558,21 @@ int rosaq_launch_shape(int32_t M, int32_t channels, int32_t in_features, int32_t
 
 int rosaq_packed_image(const rosaq_packed_t* p, int32_t which, void* out_host, size_t* bytes) {
   if (!p || !bytes) return fail(ROSAQ_ERR_NULL, "handle or bytes is NULL");
-  if (which != 0 && which != 1) return fail(ROSAQ_ERR_ARG, "which must be 0 (fp16 fragments) or 1 (low-bit records)");
+  if (which < 0 || which > 3)
+    return fail(ROSAQ_ERR_ARG, "which must be 0 / 1 (fp16 fragments / low-bit records rebuilt on the host) or 2 / 3 "
+                               "(the same two read back from the device)");
+  if (which >= 2) {
+    if (p->host_only) return fail(ROSAQ_ERR_HOSTONLY, "handle was packed with host_only");
+    const size_t tiles = (static_cast<size_t>(p->c.N) + 127) / 128 * 8;
+    const size_t need = which == 2 ? tiles * (p->c.K / kKStep) * 64 * 16
+                                   : tiles * p->c.G * ((p->c.bits == 4 ? 256 : 192) + 16) * 4;
+    if (out_host) {
+      if (*bytes < need) { *bytes = need; return fail(ROSAQ_ERR_WORKSPACE, "image buffer too small"); }
+      if (need) ROSAQ_HIP(hipMemcpy(out_host, which == 2 ? p->d_wS : p->d_wq, need, hipMemcpyDeviceToHost));
+    }
+    *bytes = need;
+    return ROSAQ_OK;
+  }
   DeviceImage img;
   try {
     build_device_image(p->c, nullptr, &img);

@@ -32,6 +32,11 @@ struct Canonical {
   std::vector<uint16_t> zeros;        // [N x G] fp16 (integer valued)
 };
 
+// Pieces of the offline step that also serve the device path: input checks, and the salient set
+// with the storage order (fills the shape fields, salient_idx, perm, pos).
+int pack_validate(const rosaq_pack_desc& d, std::string* err);
+void pack_select(const rosaq_pack_desc& d, Canonical* c);
+
 // Sec. 3.1-3.3 on the host.  Returns ROSAQ_OK or an error code with `err` filled.
 // `rotated16` (optional): What = fp16(W Q) [N x D] already computed elsewhere (the device path).
 int pack_host(const rosaq_pack_desc& d, Canonical* out, std::string* err,
@@ -103,6 +108,24 @@ int launch_rotate_weights_f64(const void* W_dev, const void* Q_dev, void* out_de
                               int headwise, void* stream);
 int launch_stream_probe(const void* src, const void* shared, int workgroups, int threads, int w_kib,
                         int x_kib, int shared_kib, void* sink, void* stream);
+
+// Offline step on the device (rosaq_quant.hip): What16 [N x D] fp16 (device) -> fragment images and
+// canonical arrays (all device pointers; `flag` is one word that is set if What16 holds Inf / NaN).
+struct QuantPackArgs {
+  const void* what16;
+  int N, D, K, bits;
+  const int32_t* perm;   // [D] storage position -> rotated channel
+  void* wS_image;        // [tiles][K/32][64] x 16 B
+  void* wq_image;        // records [tiles][G]
+  void* W_S;             // fp16 [N x K]
+  void* codes;           // uint8 [N x (D-K)]
+  void* scales;          // fp16 [N x G]
+  void* zeros;           // fp16 [N x G]
+  void* flag;
+};
+int launch_quantize_pack(const QuantPackArgs& a, void* stream);
+int launch_rotation_image(const void* Q_dev, int D, int headwise, const int32_t* perm_dev, void* qf_image,
+                          void* stream);
 
 int pca_headwise_device(const void* X_dev, int n_cal, int D, int64_t ldx, float* Q_host,
                         double* eig_host, void* stream);

@@ -148,58 +148,13 @@ void rotate_headwise(const rosaq_pack_desc& d, std::vector<double>* out) {
 
 }  // namespace
 
-int pack_host(const rosaq_pack_desc& d, Canonical* c, std::string* err,
-              const std::vector<uint16_t>* rotated16) {
+// Salient channels (Sec. 3.2; per-head and ablation rules of the appendices) and the storage
+// order [salient ; rest ascending].  Fills the shape fields, salient_idx, perm and pos.
+void pack_select(const rosaq_pack_desc& d, Canonical* c) {
   const int N = d.out_features, D = d.in_features, K = d.K;
   c->N = N; c->D = D; c->K = K; c->bits = d.bits; c->q_mode = d.q_mode;
   c->G = (D - K) / kGroup;
-
-  // input checks that need the data
-  for (int i = 0; i < D; ++i)
-    if (!std::isfinite(d.eigenvalues[i])) { *err = "eigenvalues contain NaN/Inf"; return ROSAQ_ERR_NONFINITE; }
-  for (int n = 0; n < N; ++n)
-    for (int k = 0; k < D; ++k)
-      if (((d.W[static_cast<size_t>(n) * d.ldw + k] >> 10) & 31) == 31) {
-        *err = "W contains NaN/Inf"; return ROSAQ_ERR_NONFINITE;
-      }
-  if (d.q_mode != ROSAQ_Q_NONE) {
-    const size_t nq = d.q_mode == ROSAQ_Q_FULL ? static_cast<size_t>(D) * D
-                                               : static_cast<size_t>(D) * kHeadDim;
-    for (size_t i = 0; i < nq; ++i)
-      if (!std::isfinite(d.Q[i])) { *err = "Q contains NaN/Inf"; return ROSAQ_ERR_NONFINITE; }
-  }
-
-  // 1. rotate, round once to fp16
-  std::vector<uint16_t> what_local;
-  if (rotated16 == nullptr) what_local.resize(static_cast<size_t>(N) * D);
-  std::vector<uint16_t>& what_rw = what_local;
-  if (rotated16 != nullptr) {
-    for (uint16_t h : *rotated16)
-      if (((h >> 10) & 31) == 31) { *err = "rotated weight overflows fp16"; return ROSAQ_ERR_NONFINITE; }
-  } else if (d.q_mode == ROSAQ_Q_NONE) {
-    for (int n = 0; n < N; ++n)
-      std::memcpy(&what_rw[static_cast<size_t>(n) * D], d.W + static_cast<size_t>(n) * d.ldw,
-                  sizeof(uint16_t) * D);
-  } else {
-    std::vector<double> rot;
-    try {
-      if (d.q_mode == ROSAQ_Q_FULL) rotate_full(d, &rot); else rotate_headwise(d, &rot);
-    } catch (const std::bad_alloc&) { *err = "out of host memory"; return ROSAQ_ERR_NOMEM; }
-    std::atomic<bool> bad{false};
-    parallel_rows(N, [&](int lo, int hi) {
-      bool local_bad = false;
-      for (size_t i = static_cast<size_t>(lo) * D; i < static_cast<size_t>(hi) * D; ++i) {
-        what_rw[i] = f64_to_f16(rot[i]);
-        if (((what_rw[i] >> 10) & 31) == 31) local_bad = true;
-      }
-      if (local_bad) bad.store(true, std::memory_order_relaxed);
-    });
-    if (bad.load()) { *err = "rotated weight overflows fp16"; return ROSAQ_ERR_NONFINITE; }
-  }
-  const std::vector<uint16_t>& what = rotated16 ? *rotated16 : what_local;
-
-  // 2. salient channels (Sec. 3.2; per-head and ablation rules of the appendices).
-  //    Every rule ranks channels by eigenvalue with ties going to the lower channel.
+  // Every rule ranks channels by eigenvalue with ties going to the lower channel.
   std::vector<char> is_sal(D, 0);
   {
     const double* lam = d.eigenvalues;
@@ -248,6 +203,73 @@ int pack_host(const rosaq_pack_desc& d, Canonical* c, std::string* err,
   for (int ch = 0; ch < D; ++ch) if (!is_sal[ch]) c->perm.push_back(ch);
   c->pos.assign(D, 0);
   for (int p = 0; p < D; ++p) c->pos[c->perm[p]] = p;
+}
+
+// Input checks that need the data: every eigenvalue, weight and rotation entry finite.
+int pack_validate(const rosaq_pack_desc& d, std::string* err) {
+  const int N = d.out_features, D = d.in_features;
+  for (int i = 0; i < D; ++i)
+    if (!std::isfinite(d.eigenvalues[i])) { *err = "eigenvalues contain NaN/Inf"; return ROSAQ_ERR_NONFINITE; }
+  std::atomic<bool> bad{false};
+  parallel_rows(N, [&](int lo, int hi) {
+    bool local = false;
+    for (int n = lo; n < hi; ++n)
+      for (int k = 0; k < D; ++k)
+        if (((d.W[static_cast<size_t>(n) * d.ldw + k] >> 10) & 31) == 31) local = true;
+    if (local) bad.store(true, std::memory_order_relaxed);
+  });
+  if (bad.load()) { *err = "W contains NaN/Inf"; return ROSAQ_ERR_NONFINITE; }
+  if (d.q_mode != ROSAQ_Q_NONE) {
+    const int rows = d.q_mode == ROSAQ_Q_FULL ? D : kHeadDim;    // Q as [D][rows]
+    parallel_rows(D, [&](int lo, int hi) {
+      bool local = false;
+      for (size_t i = static_cast<size_t>(lo) * rows; i < static_cast<size_t>(hi) * rows; ++i)
+        if (!std::isfinite(d.Q[i])) local = true;
+      if (local) bad.store(true, std::memory_order_relaxed);
+    });
+    if (bad.load()) { *err = "Q contains NaN/Inf"; return ROSAQ_ERR_NONFINITE; }
+  }
+  return ROSAQ_OK;
+}
+
+int pack_host(const rosaq_pack_desc& d, Canonical* c, std::string* err,
+              const std::vector<uint16_t>* rotated16) {
+  const int N = d.out_features, D = d.in_features, K = d.K;
+  const int rcv = pack_validate(d, err);
+  if (rcv != ROSAQ_OK) return rcv;
+  c->G = (D - K) / kGroup;
+
+  // 1. rotate, round once to fp16
+  std::vector<uint16_t> what_local;
+  if (rotated16 == nullptr) what_local.resize(static_cast<size_t>(N) * D);
+  std::vector<uint16_t>& what_rw = what_local;
+  if (rotated16 != nullptr) {
+    for (uint16_t h : *rotated16)
+      if (((h >> 10) & 31) == 31) { *err = "rotated weight overflows fp16"; return ROSAQ_ERR_NONFINITE; }
+  } else if (d.q_mode == ROSAQ_Q_NONE) {
+    for (int n = 0; n < N; ++n)
+      std::memcpy(&what_rw[static_cast<size_t>(n) * D], d.W + static_cast<size_t>(n) * d.ldw,
+                  sizeof(uint16_t) * D);
+  } else {
+    std::vector<double> rot;
+    try {
+      if (d.q_mode == ROSAQ_Q_FULL) rotate_full(d, &rot); else rotate_headwise(d, &rot);
+    } catch (const std::bad_alloc&) { *err = "out of host memory"; return ROSAQ_ERR_NOMEM; }
+    std::atomic<bool> bad{false};
+    parallel_rows(N, [&](int lo, int hi) {
+      bool local_bad = false;
+      for (size_t i = static_cast<size_t>(lo) * D; i < static_cast<size_t>(hi) * D; ++i) {
+        what_rw[i] = f64_to_f16(rot[i]);
+        if (((what_rw[i] >> 10) & 31) == 31) local_bad = true;
+      }
+      if (local_bad) bad.store(true, std::memory_order_relaxed);
+    });
+    if (bad.load()) { *err = "rotated weight overflows fp16"; return ROSAQ_ERR_NONFINITE; }
+  }
+  const std::vector<uint16_t>& what = rotated16 ? *rotated16 : what_local;
+
+  // 2. salient channels and storage order
+  pack_select(d, c);
 
   // 3-4. split and quantise (Eq. 3, Sec. 3.3)
   const int G = c->G, C = D - K;

@@ -504,3 +504,44 @@ def test_dense_rotation_with_48_channel_tiles(rot_mt):
     check_output(y, lay["x"], Q, ref)
     check_output(y_default, lay["x"], Q, ref)
     p.free()
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("mode,N,D,K,rule", [(O.MODE_HEADWISE, 200, 512, 128, O.RULE_TOP), (O.MODE_FULL, 130, 384, 0, O.RULE_TOP),
+                                             (O.MODE_NONE, 48, 256, 256, O.RULE_TOP), (O.MODE_HEADWISE, 96, 512, 256, O.RULE_TOP_AND_BOTTOM),
+                                             (O.MODE_FULL, 260, 512, 128, O.RULE_BOTTOM)])
+def test_device_pack_equals_host_pack_and_oracle(bits, mode, N, D, K, rule):
+    """The offline step on the GPU (rotation, quantiser, images) against the oracle's canonical arrays,
+    and the fragment images it leaves in device memory against the ones the host builder makes from
+    those arrays: bit for bit, padding rows included."""
+    print(f"case device pack bits={bits} mode={mode} N={N} D={D} K={K} rule={rule}", flush=True)
+    lay, Q, lam = make_case(200 + N, 8, D, N, 300, mode)
+    ref = O.pack(lay["W"], Q, lam, K, bits, mode, rule=rule)
+    p = B.rosaq_pack_weights(lay["W"], Q, lam, K, bits, mode, select_rule=rule)
+    h = B.rosaq_pack_weights(lay["W"], Q, lam, K, bits, mode, select_rule=rule, host_only=True)
+    try:
+        check_pack(p, ref)
+        check_pack(h, ref)
+        for which in (0, 1):
+            dev_img = B.rosaq_packed_image(p, which + 2)
+            host_img = B.rosaq_packed_image(h, which)
+            assert dev_img.shape == host_img.shape and np.array_equal(dev_img, host_img), which
+    finally:
+        p.free()
+        h.free()
+
+
+def test_device_pack_strided_weights_and_overflow():
+    """ldw > D goes through a pitched upload; a rotation that overflows fp16 is reported."""
+    lay, Q, lam = make_case(77, 8, 256, 40, 300, O.MODE_FULL)
+    Wp = np.zeros((40, 320), np.float16)
+    Wp[:, :256] = lay["W"]
+    ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_FULL)
+    p = B.rosaq_pack_weights(Wp, Q, lam, 128, 4, B.Q_FULL, ldw=320, in_features=256)
+    try:
+        check_pack(p, ref)
+    finally:
+        p.free()
+    with pytest.raises(B.RosaqError) as e:
+        B.rosaq_pack_weights(lay["W"], Q * np.float32(1e7), lam, 128, 4, B.Q_FULL)
+    assert B.ERR_NAMES[e.value.code] == "NONFINITE"
