@@ -270,15 +270,15 @@ def decode_workload(torch, steps, warmup, absorbed=False):
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     qkv = [B.BatchArgs([lay[n] for n in "qkv"], [y.data_ptr() for y in y_d[:3]], [y.stride(0) for y in y_d[:3]])
            for lay in layers]
-    gu = [B.BatchArgs([lay["gate"], lay["up"]], [y.data_ptr() for y in y_f], [y.stride(0) for y in y_f])
-          for lay in layers]
 
     def step():
         sp = T.current_stream_ptr()
         for l, lay in enumerate(layers):
             B.rosaq_linear_batch(qkv[l], x.data_ptr(), M, x.stride(0), ws.data_ptr(), ws.numel(), sp)
             T.linear(lay["o"], x, y_d[3], ws)
-            B.rosaq_linear_batch(gu[l], x.data_ptr(), M, x.stride(0), ws.data_ptr(), ws.numel(), sp)
+            # gate and up in one launch, silu(gate) * up applied in its epilogue
+            B.rosaq_linear_swiglu(lay["gate"], lay["up"], x.data_ptr(), M, x.stride(0), y_f[0].data_ptr(),
+                                  y_f[0].stride(0), ws.data_ptr(), ws.numel(), sp)
             T.linear(lay["down"], xh, y_d[3], ws)
 
     # fp16: the same seven linears per layer as separate vendor GEMMs, and with q/k/v and gate/up fused
@@ -314,16 +314,17 @@ def decode_workload(torch, steps, warmup, absorbed=False):
 
     per_layer = (4 * d * row_bytes(d, 4) + 2 * f * row_bytes(d, 4) + d * row_bytes(f, 4)   # packed weights
                  + (0 if ab else 2 * 2 * 128 * d + 2 * d * d)                       # two head-wise + one dense rotation
-                 + 2 * M * (4 * d + 4 * d) + 2 * M * (d + 2 * f) + 2 * M * (f + d))  # x and y of the four calls
+                 + 2 * M * (4 * d + 4 * d) + 2 * M * (d + f) + 2 * M * (f + d))      # x and y of the four calls
     fp16_layer = 2 * (4 * d * d + 3 * d * f) + 2 * M * (2 * d + 4 * d) + 2 * M * (d + 2 * f) + 2 * M * (f + d)
     ms = t["median"]
     out = {
         "workload": "llama7b_decode_linears_M64_int4" + ("_rotations_absorbed" if ab else ""),
         "layers": L, "linears_per_step": 7 * L, "M": M,
-        "calls_per_layer": ("rosaq_linear_batch(q,k,v) + rosaq_linear(o) + rosaq_linear_batch(gate,up) + "
+        "calls_per_layer": ("rosaq_linear_batch(q,k,v) + rosaq_linear(o) + rosaq_linear_swiglu(gate,up) + "
                             "rosaq_linear(down): inputs arrive rotated, run time only permutes them") if ab else
                            ("rosaq_linear_batch(q,k,v; head-wise) + rosaq_linear_headwise(o) + "
-                            "rosaq_linear_batch(gate,up; dense 4096^2 rotation) + rosaq_linear(down; no rotation)"),
+                            "rosaq_linear_swiglu(gate,up; dense 4096^2 rotation, silu(gate)*up in the epilogue) + "
+                            "rosaq_linear(down; no rotation)"),
         "steps_timed": steps, "ms_per_step": round(ms, 4), "ms_per_step_p10": round(t["p10"], 4),
         "ms_per_step_p90": round(t["p90"], 4), "total_s": round(ms * steps * 1e-3, 4),
         "tokens_per_s": round(M / (ms * 1e-3), 1),
@@ -333,7 +334,7 @@ def decode_workload(torch, steps, warmup, absorbed=False):
         "frac_of_hbm_peak": round(per_layer * L / ms / 1e6 / HBM_PEAK_GBS, 4),
         "packed_GB_resident": round(packed_bytes / 1e9, 3),
         "setup_s_one_layer_incl_synthetic_weights": round(t_pack, 1),
-        "fp16": {"impl": "torch.matmul fp16 (vendor GEMM), one hipGraph per step",
+        "fp16": {"impl": "torch.matmul fp16 (vendor GEMM), one hipGraph per step; no activation kernel",
                  "ms_per_step_4_gemms_per_layer_fused_qkv_gateup": round(t16f["median"], 4),
                  "ms_per_step_7_gemms_per_layer": round(t16s["median"], 4),
                  "GB_per_step": round(fp16_layer * L / 1e9, 3),

@@ -174,6 +174,20 @@ int rosaq_linear_batch(const rosaq_packed_t* const* layers, int32_t count, const
                        int32_t M, int64_t ldx, void* const* y_dev, const int64_t* ldy,
                        void* ws_dev, size_t ws_bytes, void* hip_stream);
 
+/* rosaq_linear_swiglu - the gated pair of the FFN in one pass:
+ *     y = silu(xhat What_gate^T) * (xhat What_up^T),   silu(t) = t / (1 + exp(-t)),
+ * both products accumulated in fp32, the gate applied in fp32, y rounded to fp16 once.  The up and
+ * gate projections read the same input through the same rotation (weight splitting appendix:
+ * W_U and W_G are split alike), so xhat is computed once and both weights stream in one launch; the
+ * two [M x N] intermediates never reach memory.
+ *   gate, up  handles with identical N, D, K, bits, q_mode and rotation (as for rosaq_linear_batch)
+ *   y_dev     DEVICE fp16 [M x N], row stride ldy
+ * Other arguments and rules as rosaq_linear (serves every q_mode; the launch is never split over
+ * workgroups).  Errors: those of rosaq_linear, MODE (the layers differ). */
+int rosaq_linear_swiglu(const rosaq_packed_t* gate, const rosaq_packed_t* up, const void* x_dev, int32_t M,
+                        int64_t ldx, void* y_dev, int64_t ldy, void* ws_dev, size_t ws_bytes,
+                        void* hip_stream);
+
 /* Shape and storage facts of a handle (any output pointer may be NULL). */
 int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* K,
                       int32_t* bits, int32_t* group, int32_t* q_mode,

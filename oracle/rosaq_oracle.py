@@ -22,6 +22,8 @@ Steps (paper passages they follow):
   pack                      Eq. 3 split [R_S^T W_S ; Q(R_N^T W_N)]
   linear_ref                Eq. 3 evaluated in fp64 on the stored representation
                             (Eq. 6 when the rotation is block diagonal)
+  swiglu_ref                silu(gate) * up on two such layers (the FFN around W_G, W_U of the
+                            weight-splitting appendix)
 
 Pins (tests/test_oracle_*.py): orthogonality, trace and reconstruction of the
 eigen-decomposition, agreement with LAPACK, a closed form with orthogonal
@@ -375,6 +377,20 @@ def linear_ref(x16, Q, p: dict, q_round: bool = True) -> np.ndarray:
     Qr = round_rotation(Q, mode) if q_round else Q
     xhat = rotate(x16, Qr, mode)
     return xhat[:, p["perm"]] @ stored_weights(p).T
+
+
+def silu(t) -> np.ndarray:
+    """t / (1 + exp(-t)) in fp64, written so that large |t| neither overflows nor loses digits."""
+    t = as_f64(t)
+    e = np.exp(-np.abs(t))                       # in (0, 1]
+    return np.where(t >= 0, t / (1.0 + e), t * e / (1.0 + e))
+
+
+def swiglu_ref(x16, Q, p_gate: dict, p_up: dict) -> np.ndarray:
+    """The gated pair of the FFN on two stored layers that share input and rotation (the up and
+    gate projections are split alike, weight-splitting appendix): silu(y_gate) * y_up with both
+    outputs the fp64 evaluation of Eq. 3, nothing rounded in between."""
+    return silu(linear_ref(x16, Q, p_gate)) * linear_ref(x16, Q, p_up)
 
 
 def tolerance_scale(x16, p: dict) -> np.ndarray:

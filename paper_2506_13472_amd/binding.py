@@ -22,7 +22,7 @@ ERR_NAMES = {0: "OK", -1: "NULL", -2: "SHAPE", -3: "ARG", -4: "MODE", -5: "ALIGN
 LIB_PATH = os.environ.get("ROSAQ_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "librosaq.so")
 
 EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_workspace_bytes_batch", "rosaq_workspace_bytes_min", "rosaq_linear", "rosaq_linear_headwise",
-            "rosaq_linear_headwise_static", "rosaq_linear_batch", "rosaq_stream_probe", "rosaq_packed_clone", "rosaq_pca_headwise",
+            "rosaq_linear_headwise_static", "rosaq_linear_batch", "rosaq_linear_swiglu", "rosaq_stream_probe", "rosaq_packed_clone", "rosaq_pca_headwise",
             "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_launch_shape", "rosaq_block_map", "rosaq_packed_image", "rosaq_free",
             "rosaq_last_error"]
 
@@ -78,6 +78,8 @@ def lib() -> C.CDLL:
         L.rosaq_linear_batch.argtypes = [C.POINTER(vp), i32, vp, i32, i64, C.POINTER(vp),
                                          C.POINTER(i64), vp, sz, vp]
         L.rosaq_linear_batch.restype = C.c_int
+        L.rosaq_linear_swiglu.argtypes = [vp, vp, vp, i32, i64, vp, i64, vp, sz, vp]
+        L.rosaq_linear_swiglu.restype = C.c_int
         L.rosaq_pca_headwise.argtypes = [vp, i32, i32, i64, vp, vp, vp]
         L.rosaq_pca_headwise.restype = C.c_int
         L.rosaq_stream_probe.argtypes = [vp, sz, vp, sz, sz, i32, i32, vp, sz, vp]
@@ -221,6 +223,11 @@ def rosaq_linear_batch(args: BatchArgs, x_ptr: int, M: int, ldx: int, ws_ptr: in
                        stream: int = 0):
     _check(lib().rosaq_linear_batch(args.layers, args.count, x_ptr, M, ldx, args.ys, args.ldys,
                                     ws_ptr, ws_bytes, stream))
+
+
+def rosaq_linear_swiglu(gate: Packed, up: Packed, x_ptr: int, M: int, ldx: int, y_ptr: int, ldy: int,
+                        ws_ptr: int, ws_bytes: int, stream: int = 0):
+    _check(lib().rosaq_linear_swiglu(gate.handle, up.handle, x_ptr, M, ldx, y_ptr, ldy, ws_ptr, ws_bytes, stream))
 
 
 def rosaq_pca_headwise(x_ptr: int, n_cal: int, D: int, ldx: int, stream: int = 0):

@@ -223,7 +223,8 @@ static int check_device(const rosaq_packed_t* const* ps, int count) {
 
 // y_i = xhat W_i^T for `count` layers that share the xhat fragments in the workspace.
 static int run_main_gemm(const rosaq_packed_t* const* ps, int count, const WsPlan& w, int M,
-                         void* const* ys, const int64_t* ldys, char* ws, size_t ws_bytes, void* stream) {
+                         void* const* ys, const int64_t* ldys, char* ws, size_t ws_bytes, void* stream,
+                         bool swiglu = false) {
   const Canonical& c = ps[0]->c;
   GemmArgs a{};
   a.xf = ws + (c.q_mode == ROSAQ_Q_FULL ? w.xf_b : w.xf_a);
@@ -238,6 +239,7 @@ static int run_main_gemm(const rosaq_packed_t* const* ps, int count, const WsPla
   a.bits = c.bits; a.out_frag = 0;
   a.part = ws + w.part; a.part_bytes = ws_bytes > w.part ? ws_bytes - w.part : 0;
   a.tickets = ws + w.tickets + kTicketsPerLaunch * sizeof(uint32_t); a.ticket_count = kTicketsPerLaunch;
+  a.swiglu = swiglu ? 1 : 0;
   return launch_gemm(a, g_tune, stream);
 }
 
@@ -280,13 +282,13 @@ static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_
 
 static int run_call(const rosaq_packed_t* const* ps, int count, const void* x_dev, int M,
                     int64_t ldx, void* const* ys, const int64_t* ldys, char* ws, size_t ws_bytes,
-                    const WsPlan& w, void* hip_stream) {
+                    const WsPlan& w, void* hip_stream, bool swiglu = false) {
   if (g_tune_stages & 1) {
     const int rc = run_prologue(ps[0], w, x_dev, M, ldx, ws, ws_bytes, hip_stream);
     if (rc != ROSAQ_OK) return rc;
   }
   if (!(g_tune_stages & 2)) return ROSAQ_OK;
-  return run_main_gemm(ps, count, w, M, ys, ldys, ws, ws_bytes, hip_stream);
+  return run_main_gemm(ps, count, w, M, ys, ldys, ws, ws_bytes, hip_stream, swiglu);
 }
 
 static uint64_t fnv1a(uint64_t h, const void* data, size_t n) {
@@ -445,6 +447,25 @@ int rosaq_linear_batch(const rosaq_packed_t* const* layers, int32_t count, const
   }
   if (check_device(layers, count) != ROSAQ_OK) return ROSAQ_ERR_HOSTONLY;
   return run_call(layers, count, x_dev, M, ldx, y_dev, ldy, static_cast<char*>(ws_dev), ws_bytes, w, hip_stream);
+}
+
+int rosaq_linear_swiglu(const rosaq_packed_t* gate, const rosaq_packed_t* up, const void* x_dev, int32_t M,
+                        int64_t ldx, void* y_dev, int64_t ldy, void* ws_dev, size_t ws_bytes,
+                        void* hip_stream) {
+  if (!gate || !up) return fail(ROSAQ_ERR_NULL, "a layer handle is NULL");
+  const Canonical &a = gate->c, &b = up->c;
+  if (a.N != b.N || a.D != b.D || a.K != b.K || a.bits != b.bits || a.q_mode != b.q_mode ||
+      gate->rot_fingerprint != up->rot_fingerprint)
+    return fail(ROSAQ_ERR_MODE, "gate and up must share N, D, K, bits and the rotation");
+  WsPlan w;
+  const bool headwise = a.q_mode == ROSAQ_Q_HEADWISE;
+  int rc = check_call(gate, x_dev, M, ldx, y_dev, ldy, ws_dev, ws_bytes, headwise, &w);
+  if (rc != ROSAQ_OK) return rc;
+  const rosaq_packed_t* ps[2] = {gate, up};
+  if (check_device(ps, 2) != ROSAQ_OK) return ROSAQ_ERR_HOSTONLY;
+  void* ys[2] = {y_dev, y_dev};
+  const int64_t ldys[2] = {ldy, ldy};
+  return run_call(ps, 2, x_dev, M, ldx, ys, ldys, static_cast<char*>(ws_dev), ws_bytes, w, hip_stream, true);
 }
 
 int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* K, int32_t* bits,

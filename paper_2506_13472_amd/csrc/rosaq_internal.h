@@ -82,6 +82,7 @@ struct GemmArgs {
   int ticket_count = 0;
   void* zero_ptr = nullptr;   // 32-bit words this launch clears for a later launch of the call
   int zero_count = 0;
+  int swiglu = 0;             // nseg == 2 layers of equal N: store silu(seg 0) * seg 1 to seg[0].out
 };
 constexpr int kMaxSplits = 16;
 constexpr int kTicketsPerLaunch = 4096;   // ticket words per GEMM launch kept in the workspace

@@ -120,6 +120,9 @@ struct GemmDev {
   unsigned* tickets;       // [tiles], zero before the launch and zero again after it
   unsigned* zero_ptr;      // words this launch clears for a later launch (may be null)
   int zero_count;
+  // gated pair (two layers of equal width, unsplit): the tile list alternates layer 0 / layer 1
+  // tiles of the same channels, and the epilogue stores silu(layer 0) * layer 1 to seg[0].out
+  int swiglu;
 };
 
 // Partial tiles and tickets travel between workgroups that may sit on different XCDs, whose L2
@@ -203,6 +206,7 @@ __device__ __forceinline__ void locate_tile(const GemmDev& p, int T, int& si, in
   si = 0;
   local = T;
   if (p.nseg == 1) return;   // the common case stays cheap (uniform branch)
+  if (p.swiglu) { si = T & 1; local = T >> 1; return; }
 #pragma unroll
   for (int i = 1; i < kMaxBatch; ++i)
     if (i < p.nseg && T >= p.seg[i - 1].tile_end) si = i;
@@ -506,6 +510,47 @@ void gemm_kernel(GemmDev p) {
     }
   }
   }   // BITS != 16
+
+  // ---- gated pair: out = silu(gate) * up, both sums still in fp32, one rounding to fp16 ------
+  if constexpr (kRedNT % 2 == 0) {
+    if (p.swiglu) {
+      constexpr int kPairs = (kRedNT / 2) * MT;
+      const GemmSeg sg = p.seg[0];
+#pragma unroll
+      for (int pass = 0; pass < kRedPasses; ++pass) {
+        if (pass > 0) __syncthreads();
+#pragma unroll
+        for (int nt = 0; nt < kRedNT; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const floatx4 v = acc[pass * kRedNT + nt][mt];
+            red[wave][nt * MT + mt][lane] = make_float4(v[0], v[1], v[2], v[3]);
+          }
+        __syncthreads();
+        for (int ps = wave; ps < kPairs; ps += WPB) {
+          const int j = ps / MT, mt = ps - j * MT;
+          float4 g = red[0][(2 * j) * MT + mt][lane], u = red[0][(2 * j + 1) * MT + mt][lane];
+#pragma unroll
+          for (int w = 1; w < WPB; ++w) {
+            const float4 a = red[w][(2 * j) * MT + mt][lane], b = red[w][(2 * j + 1) * MT + mt][lane];
+            g.x += a.x; g.y += a.y; g.z += a.z; g.w += a.w;
+            u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
+          }
+          const float gv[4] = {g.x, g.y, g.z, g.w}, uv[4] = {u.x, u.y, u.z, u.w};
+          const int n = ((tile0 + pass * kRedNT + 2 * j) >> 1) * kTileN + (lane & 15);
+          if (n < sg.N) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int m = (mtile0 + mt) * 16 + 4 * (lane >> 4) + i;
+              const float act = gv[i] / (1.0f + __expf(-gv[i]));       // silu
+              if (m < p.M) sg.out[static_cast<int64_t>(m) * sg.ldo + n] = static_cast<_Float16>(act * uv[i]);
+            }
+          }
+        }
+      }
+      return;
+    }
+  }
 
   // ---- sum the waves of this workgroup through LDS in wave order -----------------------
   constexpr int kSlots = kRedNT * MT;
@@ -981,13 +1026,15 @@ static int launch_gemm_shape(const GemmArgs& a, const GemmShape& sh, void* strea
     d.seg[i].N = sa.N;
     d.seg[i].tile_end = tiles;
   }
+  if (a.swiglu && (sh.nt & 1)) return 1;   // pairs of tiles need an even tile count per workgroup
   d.chunks = (tiles + sh.nt - 1) / sh.nt;
   d.mgroups = ((a.M + 15) / 16 + sh.mt - 1) / sh.mt;
-  d.splits = sh.splits;
+  d.splits = a.swiglu ? 1 : sh.splits;
   d.part = static_cast<float4*>(a.part);
   d.tickets = static_cast<unsigned*>(a.tickets);
   d.zero_ptr = static_cast<unsigned*>(a.zero_ptr);
   d.zero_count = a.zero_count;
+  d.swiglu = a.swiglu;
   const int bits = a.G == 0 ? 16 : a.bits;
   hipStream_t st = static_cast<hipStream_t>(stream);
 #define ROSAQ_CASE(B, MT_, NT_, W)                                              \
@@ -1024,9 +1071,24 @@ int launch_gemm(const GemmArgs& a, const GemmTune& tune, void* stream) {
     return pick_gemm_shape(a.M, tiles_total, a.KS * kKStep, bits, t, a.part ? a.part_bytes : 0,
                            a.tickets ? a.ticket_count : 0, a.ks_s);
   };
-  int rc = launch_gemm_shape(a, shape(tune), stream);
+  GemmTune t0 = tune;
+  if (a.swiglu) {
+    // a gated pair runs unsplit with an even number of channel tiles per workgroup
+    t0.splits = 1;
+    const GemmShape s0 = shape(t0);
+    if (s0.nt & 1) t0.nt = s0.nt == 3 ? 4 : 2;
+  }
+  int rc = launch_gemm_shape(a, shape(t0), stream);
   // a forced combination that no kernel is built for falls back to the heuristic's choice
-  if (rc == 1) rc = launch_gemm_shape(a, shape(GemmTune{}), stream);
+  if (rc == 1) {
+    GemmTune t1{};
+    if (a.swiglu) {
+      t1.splits = 1;
+      const GemmShape s1 = shape(t1);
+      if (s1.nt & 1) t1.nt = s1.nt == 3 ? 4 : 2;
+    }
+    rc = launch_gemm_shape(a, shape(t1), stream);
+  }
   if (rc == 1) {
     set_error("no kernel for this bits / tile combination");
     return ROSAQ_ERR_ARG;

@@ -188,3 +188,26 @@ def test_tolerance_scale_square_case_axes():
     # the transposed outer product and the column norms (sqrt 5, sqrt 8, 1, 4) give other numbers
     assert not np.allclose(got, got.T)
     assert not np.allclose(got[0], 5.0 * np.array([np.sqrt(5), np.sqrt(8), 1.0, 4.0]))
+
+
+def test_silu_and_swiglu_against_closed_forms_and_a_library_routine():
+    from scipy.special import expit
+    t = np.concatenate([np.linspace(-60, 60, 4001), [0.0, np.log(3.0), -np.log(3.0), 800.0, -800.0]])
+    got = O.silu(t)
+    assert np.allclose(got, t * expit(t), rtol=1e-14, atol=1e-300)
+    assert O.silu(0.0) == 0.0
+    assert O.silu(np.log(3.0)) == pytest.approx(np.log(3.0) * 0.75, rel=1e-15)      # sigmoid(ln 3) = 3/4
+    assert O.silu(-np.log(3.0)) == pytest.approx(-np.log(3.0) * 0.25, rel=1e-15)
+    assert O.silu(800.0) == 800.0 and O.silu(-800.0) == 0.0 and np.all(np.isfinite(got))
+    # minimum of silu: -0.27846... at t = -1.27846...
+    assert got.min() == pytest.approx(-0.2784645427610738, abs=1e-4)
+    # the pair: gate and up swapped changes the result, equal layers give silu(y) * y
+    lay = _layer(8, 4, 256, 12, 300)
+    Q, lam = O.pca_full(lay["X_cal"], "jacobi")
+    pg = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_FULL)
+    pu = O.pack(lay["W"][::-1].copy(), Q, lam, 128, 4, O.MODE_FULL)
+    yg, yu = O.linear_ref(lay["x"], Q, pg), O.linear_ref(lay["x"], Q, pu)
+    out = O.swiglu_ref(lay["x"], Q, pg, pu)
+    assert np.allclose(out, yg * expit(yg) * yu, rtol=1e-13, atol=1e-300)
+    assert not np.allclose(out, O.swiglu_ref(lay["x"], Q, pu, pg))
+    assert np.allclose(O.swiglu_ref(lay["x"], Q, pg, pg), yg * yg * expit(yg), rtol=1e-13)
