@@ -384,6 +384,7 @@ def main():
     ap.add_argument("--depth", type=int, default=0, help="tuning aid: units in flight per wave (2-4)")
     ap.add_argument("--splits", type=int, default=0, help="tuning aid: workgroups per output tile (1-16)")
     ap.add_argument("--rot", default="", help="tuning aid: mt,nt,depth of the dense-rotation launch")
+    ap.add_argument("--rot-splits", type=int, default=0, help="tuning aid: workgroups per tile of the dense rotation")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
@@ -410,6 +411,7 @@ def main():
     if args.rot:
         for key, v in zip(("rot_mt", "rot_nt", "rot_depth"), args.rot.split(",")):
             B.rosaq_tune(key, int(v))
+    B.rosaq_tune("rot_splits", args.rot_splits)
     if args.sweep:
         shapes = [s for s in SWEEP_SHAPES if not args.sweep_filter or args.sweep_filter in s[0]]
         ms = [int(v) for v in args.sweep_m.split(",")] if args.sweep_m else None

@@ -597,25 +597,40 @@ void gemm_kernel(GemmDev p) {
   if (threadIdx.x == 0)
     __hip_atomic_store(p.tickets + tile_id, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   constexpr int kAllSlots = kRedPasses * kSlots;
+  constexpr int kPerWave = (kAllSlots + WPB - 1) / WPB;       // slots a wave finishes
   const float4* tile_part = p.part + (tile_id * splits * kAllSlots) * 64 + lane;
-  for (int slot = wave; slot < kAllSlots; slot += WPB) {
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    // eight partial tiles in flight at a time, added in split order: the sum does not depend
-    // on the order in which the workgroups arrived
-    for (int sp0 = 0; sp0 < splits; sp0 += 8) {
-      float4 o[8];
+  // Every load below is unconditional (a split or slot past the end re-reads the last one and is
+  // dropped by a select when added): loads under a branch end up next to their use, and the wave
+  // would wait for each partial tile in turn instead of having them all in flight.
+  float4 v[kPerWave];
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (sp0 + j < splits) {
-          const float4* src = tile_part + (static_cast<size_t>(sp0 + j) * kAllSlots + slot) * 64;
-          o[j] = load_device_scope(src);
-        }
+  for (int i = 0; i < kPerWave; ++i) v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int sp0 = 0; sp0 < splits; sp0 += 4) {     // four partial tiles per slot in flight, added in split order
+    float4 o[kPerWave][4];
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (sp0 + j < splits) { v.x += o[j].x; v.y += o[j].y; v.z += o[j].z; v.w += o[j].w; }
+    for (int i = 0; i < kPerWave; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int slot = wave + i * WPB < kAllSlots ? wave + i * WPB : kAllSlots - 1;
+        const int sp = sp0 + j < splits ? sp0 + j : splits - 1;
+        o[i][j] = load_device_scope(tile_part + (static_cast<size_t>(sp) * kAllSlots + slot) * 64);
+      }
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bool use = sp0 + j < splits;
+        v[i].x += use ? o[i][j].x : 0.f; v[i].y += use ? o[i][j].y : 0.f;
+        v[i].z += use ? o[i][j].z : 0.f; v[i].w += use ? o[i][j].w : 0.f;
+      }
+  }
+#pragma unroll
+  for (int i = 0; i < kPerWave; ++i) {
+    const int slot = wave + i * WPB;
+    if (slot < kAllSlots) {
+      const int pass = slot / kSlots, sl = slot - pass * kSlots;
+      store_fragment(p, v[i], mtile0 + sl % MT, tile0 + pass * kRedNT + sl / MT, lane);
     }
-    const int pass = slot / kSlots, sl = slot - pass * kSlots;
-    store_fragment(p, v, mtile0 + sl % MT, tile0 + pass * kRedNT + sl / MT, lane);
   }
 }
 
