@@ -216,6 +216,24 @@ int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t*
 int rosaq_pca_headwise(const void* X_dev, int32_t n_cal, int32_t D, int64_t ldx, float* Q_host,
                        double* eigenvalues_host, void* hip_stream);
 
+/* rosaq_pca_full - the same calibration step for a layer-wise rotation (Sec. 3.1, Eq. 4): the
+ * eigenvectors of C = X^T X / n_cal over all D input channels, found as the right singular vectors
+ * of X by one-sided Jacobi rotations in fp64 on the GPU (pairs of columns of X are rotated until
+ * all are mutually orthogonal; C is never formed; eigenvalue c = |column c of X V|^2 / n_cal).
+ * Stops when the off-diagonal norm of the implied C is <= 1e-13 ||C||_F.  Results as for
+ * rosaq_pca_headwise:
+ *   Q_host            HOST fp32 [D x D] row-major, eigenvectors as columns (xhat = x Q), sorted by
+ *                     eigenvalue descending, each signed so that its largest entry is positive; with
+ *                     fewer calibration rows than channels the null space comes out as an orthonormal
+ *                     completion (any one is valid)
+ *   eigenvalues_host  HOST fp64 [D], descending, >= 0
+ *   X_dev             DEVICE fp16 [n_cal x D], row r at X + r*ldx
+ * D a multiple of 128 up to 8192 (a sweep is D - 1 launches; a 1024-channel layer takes a few
+ * tenths of a second).  Allocates its own device scratch (8 D (n_cal + D) bytes and 4 D^2 bytes of
+ * bookkeeping) and waits for the result.  Errors: NULL, SHAPE, ALIGN, HIP, NOCONVERGE. */
+int rosaq_pca_full(const void* X_dev, int32_t n_cal, int32_t D, int64_t ldx, float* Q_host,
+                   double* eigenvalues_host, void* hip_stream);
+
 /* rosaq_stream_probe - measurement aid, no arithmetic of the method: one launch of
  * `workgroups` x `threads` in which every wave reads its own contiguous share of
  * src_dev (src_bytes in total, 1 KiB per load) and every workgroup then reads

@@ -22,7 +22,7 @@ ERR_NAMES = {0: "OK", -1: "NULL", -2: "SHAPE", -3: "ARG", -4: "MODE", -5: "ALIGN
 LIB_PATH = os.environ.get("ROSAQ_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "librosaq.so")
 
 EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_workspace_bytes_batch", "rosaq_workspace_bytes_min", "rosaq_linear", "rosaq_linear_headwise",
-            "rosaq_linear_headwise_static", "rosaq_linear_batch", "rosaq_linear_swiglu", "rosaq_stream_probe", "rosaq_packed_clone", "rosaq_pca_headwise",
+            "rosaq_linear_headwise_static", "rosaq_linear_batch", "rosaq_linear_swiglu", "rosaq_stream_probe", "rosaq_packed_clone", "rosaq_pca_headwise", "rosaq_pca_full",
             "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_launch_shape", "rosaq_block_map", "rosaq_packed_image", "rosaq_free",
             "rosaq_last_error"]
 
@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
         L.rosaq_linear_swiglu.restype = C.c_int
         L.rosaq_pca_headwise.argtypes = [vp, i32, i32, i64, vp, vp, vp]
         L.rosaq_pca_headwise.restype = C.c_int
+        L.rosaq_pca_full.argtypes = [vp, i32, i32, i64, vp, vp, vp]
+        L.rosaq_pca_full.restype = C.c_int
         L.rosaq_stream_probe.argtypes = [vp, sz, vp, sz, sz, i32, i32, vp, sz, vp]
         L.rosaq_stream_probe.restype = C.c_int
         L.rosaq_packed_info.argtypes = [vp] + [C.POINTER(i32)] * 6 + [C.POINTER(sz)]
@@ -235,6 +237,14 @@ def rosaq_pca_headwise(x_ptr: int, n_cal: int, D: int, ldx: int, stream: int = 0
     Q = np.empty((max(D // 128, 0), 128, 128), np.float32)
     lam = np.empty(max(D, 0), np.float64)
     _check(lib().rosaq_pca_headwise(x_ptr, n_cal, D, ldx, _ptr(Q), _ptr(lam), stream))
+    return Q, lam
+
+
+def rosaq_pca_full(x_ptr: int, n_cal: int, D: int, ldx: int, stream: int = 0):
+    """Returns (Q fp32 [D, D], eigenvalues fp64 [D]) for device activations at x_ptr."""
+    Q = np.empty((max(D, 0), max(D, 0)), np.float32)
+    lam = np.empty(max(D, 0), np.float64)
+    _check(lib().rosaq_pca_full(x_ptr, n_cal, D, ldx, _ptr(Q), _ptr(lam), stream))
     return Q, lam
 
 

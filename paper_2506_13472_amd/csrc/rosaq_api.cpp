@@ -502,6 +502,15 @@ int rosaq_pca_headwise(const void* X_dev, int32_t n_cal, int32_t D, int64_t ldx,
   return pca_headwise_device(X_dev, n_cal, D, ldx, Q_host, eigenvalues_host, hip_stream);
 }
 
+int rosaq_pca_full(const void* X_dev, int32_t n_cal, int32_t D, int64_t ldx, float* Q_host,
+                   double* eigenvalues_host, void* hip_stream) {
+  if (!X_dev || !Q_host || !eigenvalues_host) return fail(ROSAQ_ERR_NULL, "a pointer is NULL");
+  if (n_cal < 1 || D < kGroup || D % kGroup != 0 || D > 8192 || ldx < D)
+    return fail(ROSAQ_ERR_SHAPE, "n_cal >= 1, D a multiple of 128 up to 8192, ldx >= D");
+  if (reinterpret_cast<uintptr_t>(X_dev) % 2) return fail(ROSAQ_ERR_ALIGN, "X must be 2-byte aligned");
+  return pca_full_device(X_dev, n_cal, D, ldx, Q_host, eigenvalues_host, hip_stream);
+}
+
 int rosaq_stream_probe(const void* src_dev, size_t src_bytes, const void* shared_dev,
                        size_t shared_bytes, size_t shared_bytes_per_workgroup, int32_t workgroups,
                        int32_t threads, void* sink_dev, size_t sink_bytes, void* hip_stream) {

@@ -130,6 +130,8 @@ int launch_rotation_image(const void* Q_dev, int D, int headwise, const int32_t*
 
 int pca_headwise_device(const void* X_dev, int n_cal, int D, int64_t ldx, float* Q_host,
                         double* eig_host, void* stream);
+int pca_full_device(const void* X_dev, int n_cal, int D, int64_t ldx, float* Q_host, double* eig_host,
+                    void* stream);
 
 // Library-owned scratch (rosaq_static.hip): the device address of this GPU's copy of a fixed
 // kStaticScratchBytes array, looked up once per device.

@@ -150,6 +150,111 @@ __global__ __launch_bounds__(1024) void jacobi128_kernel(const double* __restric
   if (tid == 0) sweeps_out[h] = converged ? sweep : -1;
 }
 
+// ---- layer-wise PCA (Sec. 3.1, Eq. 4) for a whole layer: one-sided Jacobi -----------------------
+// The eigenvectors of C = X^T X / n_cal are the right singular vectors of X, its eigenvalues the
+// squared column norms of X V / n_cal.  Plane rotations are applied to pairs of columns of X (kept
+// transposed, Y[c][:] = column c, so that a column is contiguous) until all columns are mutually
+// orthogonal; the same rotations accumulate in V.  C itself (D x D) is never formed and no
+// rotation touches more than two rows of Y and V, so the D / 2 disjoint pairs of a round run on
+// D / 2 workgroups with no exchange at all -- one launch per round, D - 1 rounds per sweep.
+
+// Y[c][r] = X[r][c] in fp64 (rows padded with zeros to n_pad), Vt = I.
+__global__ __launch_bounds__(256) void hestenes_init_kernel(const _Float16* __restrict__ X, int64_t ldx,
+                                                            int n_cal, int n_pad, int D,
+                                                            double* __restrict__ Y, double* __restrict__ Vt) {
+  const int c = blockIdx.x;
+  for (int r = threadIdx.x; r < n_pad; r += 256)
+    Y[static_cast<size_t>(c) * n_pad + r] = r < n_cal ? static_cast<double>(X[static_cast<int64_t>(r) * ldx + c]) : 0.0;
+  for (int j = threadIdx.x; j < D; j += 256) Vt[static_cast<size_t>(c) * D + j] = j == c ? 1.0 : 0.0;
+}
+
+// One round: workgroup k rotates the pair (p, q) that the round-robin tournament assigns to it
+// (player D - 1 stays, the others move one seat per round; seat k meets seat D - 1 - k).
+//   alpha = |y_p|^2, beta = |y_q|^2, gamma = y_p . y_q;  zeta = (beta - alpha) / (2 gamma),
+//   t = sign(zeta) / (|zeta| + sqrt(1 + zeta^2)), c = 1 / sqrt(1 + t^2), s = c t,
+//   (y_p, y_q) <- (c y_p - s y_q, s y_p + c y_q), the same for the rows p, q of Vt.
+// Pairs that are orthogonal to round-off (|gamma| <= eps sqrt(alpha beta)) are left alone.
+// gamma^2 of every pair (before its rotation) and, in the first round of a sweep, alpha^2 + beta^2
+// go to `stats` slots that a later launch adds up in a fixed order.
+__global__ __launch_bounds__(256) void hestenes_round_kernel(double* __restrict__ Y, double* __restrict__ Vt,
+                                                             int n_pad, int D, int round,
+                                                             double* __restrict__ gamma2,
+                                                             double* __restrict__ diag2) {
+  __shared__ double red[3][4];
+  const int k = blockIdx.x, tid = threadIdx.x;
+  auto player = [&](int seat) { return seat == D - 1 ? D - 1 : (seat + round) % (D - 1); };
+  const int a = player(k), b = player(D - 1 - k);
+  const int p = a < b ? a : b, q = a < b ? b : a;
+  double* yp = Y + static_cast<size_t>(p) * n_pad;
+  double* yq = Y + static_cast<size_t>(q) * n_pad;
+  double al = 0.0, be = 0.0, ga = 0.0;
+  for (int r = tid; r < n_pad; r += 256) {
+    const double u = yp[r], v = yq[r];
+    al = __builtin_fma(u, u, al); be = __builtin_fma(v, v, be); ga = __builtin_fma(u, v, ga);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    al += __shfl_down(al, o, 64); be += __shfl_down(be, o, 64); ga += __shfl_down(ga, o, 64);
+  }
+  if ((tid & 63) == 0) { red[0][tid >> 6] = al; red[1][tid >> 6] = be; red[2][tid >> 6] = ga; }
+  __syncthreads();
+  al = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+  be = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+  ga = (red[2][0] + red[2][1]) + (red[2][2] + red[2][3]);
+  if (tid == 0) {
+    gamma2[k] = ga * ga;
+    if (diag2 != nullptr) diag2[k] = al * al + be * be;
+  }
+  if (!(fabs(ga) > 2.220446049250313e-16 * sqrt(al * be))) return;   // also alpha or beta zero, NaN
+  const double zeta = (be - al) / (2.0 * ga);
+  const double t = zeta == 0.0 ? 1.0 : copysign(1.0, zeta) / (fabs(zeta) + hypot(1.0, zeta));
+  const double c = 1.0 / sqrt(1.0 + t * t), s = c * t;
+  for (int r = tid; r < n_pad; r += 256) {
+    const double u = yp[r], v = yq[r];
+    yp[r] = c * u - s * v;
+    yq[r] = s * u + c * v;
+  }
+  double* vp = Vt + static_cast<size_t>(p) * D;
+  double* vq = Vt + static_cast<size_t>(q) * D;
+  for (int j = tid; j < D; j += 256) {
+    const double u = vp[j], v = vq[j];
+    vp[j] = c * u - s * v;
+    vq[j] = s * u + c * v;
+  }
+}
+
+// out[0] = sum of gamma2[0 .. n_gamma), out[1] = sum of diag2[0 .. n_diag): one workgroup, every
+// thread adds its strided share in order and the 256 shares are added in a fixed tree.
+__global__ __launch_bounds__(256) void hestenes_sum_kernel(const double* __restrict__ gamma2, size_t n_gamma,
+                                                           const double* __restrict__ diag2, int n_diag,
+                                                           double* __restrict__ out) {
+  __shared__ double sh[2][256];
+  double g = 0.0, d = 0.0;
+  for (size_t i = threadIdx.x; i < n_gamma; i += 256) g += gamma2[i];
+  for (int i = threadIdx.x; i < n_diag; i += 256) d += diag2[i];
+  sh[0][threadIdx.x] = g; sh[1][threadIdx.x] = d;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (threadIdx.x < w) { sh[0][threadIdx.x] += sh[0][threadIdx.x + w]; sh[1][threadIdx.x] += sh[1][threadIdx.x + w]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) { out[0] = sh[0][0]; out[1] = sh[1][0]; }
+}
+
+// lambda_c = |y_c|^2 / n_cal
+__global__ __launch_bounds__(256) void hestenes_norms_kernel(const double* __restrict__ Y, int n_pad, int n_cal,
+                                                             double* __restrict__ lam) {
+  __shared__ double red[4];
+  const int c = blockIdx.x;
+  double a = 0.0;
+  for (int r = threadIdx.x; r < n_pad; r += 256) { const double u = Y[static_cast<size_t>(c) * n_pad + r]; a = __builtin_fma(u, u, a); }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) a += __shfl_down(a, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) lam[c] = ((red[0] + red[1]) + (red[2] + red[3])) / static_cast<double>(n_cal);
+}
+
 static int pca_fail(hipError_t e, const char* what) {
   set_error(std::string(what) + ": " + hipGetErrorString(e));
   return ROSAQ_ERR_HIP;
@@ -217,6 +322,82 @@ int pca_headwise_device(const void* X_dev, int n_cal, int D, int64_t ldx, float*
       const double sign = Vh[big * kH + src] < 0.0 ? -1.0 : 1.0;
       for (int i = 0; i < kH; ++i) Qh[i * kH + j] = static_cast<float>(sign * Vh[i * kH + src]);
     }
+  }
+  return ROSAQ_OK;
+}
+
+// Layer-wise PCA on the device: sweeps of D - 1 rounds until the off-diagonal part of the implied
+// second moment is below tol times its norm (sum gamma^2 <= tol^2 (sum lambda^2 / 2 + sum gamma^2),
+// measured over a sweep), then the same host bookkeeping as the head-wise route: eigenvalues
+// descending, negative round-off impossible here (norms), eigenvector signs fixed.
+int pca_full_device(const void* X_dev, int n_cal, int D, int64_t ldx, float* Q_host, double* eig_host,
+                    void* stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int n_pad = (n_cal + 3) / 4 * 4;
+  const size_t pairs = static_cast<size_t>(D) / 2, rounds = static_cast<size_t>(D) - 1;
+  double *dY = nullptr, *dV = nullptr, *dG = nullptr, *dD = nullptr, *dS = nullptr, *dL = nullptr;
+  hipError_t e = hipMalloc(&dY, static_cast<size_t>(D) * n_pad * 8);
+  if (e == hipSuccess) e = hipMalloc(&dV, static_cast<size_t>(D) * D * 8);
+  if (e == hipSuccess) e = hipMalloc(&dG, rounds * pairs * 8);
+  if (e == hipSuccess) e = hipMalloc(&dD, pairs * 8);
+  if (e == hipSuccess) e = hipMalloc(&dS, 2 * 8);
+  if (e == hipSuccess) e = hipMalloc(&dL, static_cast<size_t>(D) * 8);
+  constexpr int kMaxSweeps = 60;
+  constexpr double kTol = 1e-13;
+  bool converged = false;
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(hestenes_init_kernel, dim3(D), dim3(256), 0, st, static_cast<const _Float16*>(X_dev), ldx,
+                       n_cal, n_pad, D, dY, dV);
+    e = hipGetLastError();
+  }
+  for (int sweep = 0; e == hipSuccess && sweep < kMaxSweeps && !converged; ++sweep) {
+    for (size_t r = 0; r < rounds && e == hipSuccess; ++r) {
+      hipLaunchKernelGGL(hestenes_round_kernel, dim3(static_cast<unsigned>(pairs)), dim3(256), 0, st, dY, dV, n_pad,
+                         D, static_cast<int>(r), dG + r * pairs, r == 0 ? dD : nullptr);
+      e = hipGetLastError();
+    }
+    if (e != hipSuccess) break;
+    hipLaunchKernelGGL(hestenes_sum_kernel, dim3(1), dim3(256), 0, st, dG, rounds * pairs, dD, static_cast<int>(pairs), dS);
+    e = hipGetLastError();
+    double stats[2] = {0.0, 0.0};
+    if (e == hipSuccess) e = hipMemcpyAsync(stats, dS, 16, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) break;
+    // ||C||_F^2 n_cal^2 = sum alpha^2 + 2 sum gamma^2 at the start of the sweep; off^2 = 2 sum gamma^2
+    const double off2 = 2.0 * stats[0], norm2 = stats[1] + 2.0 * stats[0];
+    if (!(off2 == off2)) { e = hipErrorUnknown; break; }
+    if (off2 <= kTol * kTol * norm2) converged = true;
+  }
+  std::vector<double> V, lam(D);
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(hestenes_norms_kernel, dim3(D), dim3(256), 0, st, dY, n_pad, n_cal, dL);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) {
+    try { V.resize(static_cast<size_t>(D) * D); } catch (const std::bad_alloc&) { e = hipErrorOutOfMemory; }
+  }
+  if (e == hipSuccess) e = hipMemcpyAsync(V.data(), dV, static_cast<size_t>(D) * D * 8, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipMemcpyAsync(lam.data(), dL, static_cast<size_t>(D) * 8, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  for (double* q : {dY, dV, dG, dD, dS, dL})
+    if (q) (void)hipFree(q);
+  if (e != hipSuccess) return pca_fail(e, "rosaq_pca_full");
+  if (!converged) {
+    set_error("one-sided Jacobi did not converge within 60 sweeps");
+    return ROSAQ_ERR_NOCONVERGE;
+  }
+  std::vector<int> order(D);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return lam[a] > lam[b]; });
+  for (int j = 0; j < D; ++j) {
+    const int src = order[j];
+    const double* v = &V[static_cast<size_t>(src) * D];       // row src of Vt = eigenvector src
+    eig_host[j] = std::max(lam[src], 0.0);
+    int big = 0;
+    for (int i = 1; i < D; ++i)
+      if (std::fabs(v[i]) > std::fabs(v[big])) big = i;
+    const double sign = v[big] < 0.0 ? -1.0 : 1.0;
+    for (int i = 0; i < D; ++i) Q_host[static_cast<size_t>(i) * D + j] = static_cast<float>(sign * v[i]);
   }
   return ROSAQ_OK;
 }

@@ -197,6 +197,12 @@ def test_pca_headwise_argument_errors():
     assert _code(lambda: B.rosaq_pca_headwise(X, 64, 256, 128)) == -2
     assert _code(lambda: B.rosaq_pca_headwise(X + 1, 64, 256, 256)) == -5
     assert B.lib().rosaq_pca_headwise(X, 64, 256, 256, None, None, None) == -1
+    assert _code(lambda: B.rosaq_pca_full(0, 64, 256, 256)) == -1
+    assert _code(lambda: B.rosaq_pca_full(X, 0, 256, 256)) == -2
+    assert _code(lambda: B.rosaq_pca_full(X, 64, 200, 256)) == -2
+    assert _code(lambda: B.rosaq_pca_full(X, 64, 8320, 8320)) == -2
+    assert _code(lambda: B.rosaq_pca_full(X, 64, 256, 128)) == -2
+    assert _code(lambda: B.rosaq_pca_full(X + 1, 64, 256, 256)) == -5
 
 
 def test_launch_shape_of_the_named_workloads():

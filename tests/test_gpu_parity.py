@@ -545,3 +545,39 @@ def test_device_pack_strided_weights_and_overflow():
     with pytest.raises(B.RosaqError) as e:
         B.rosaq_pack_weights(lay["W"], Q * np.float32(1e7), lam, 128, 4, B.Q_FULL)
     assert B.ERR_NAMES[e.value.code] == "NONFINITE"
+
+
+@pytest.mark.parametrize("D,n_cal,solver", [(256, 512, "jacobi"), (256, 100, "jacobi"), (1024, 700, "lapack")])
+def test_pca_full_on_gpu_against_oracle(D, n_cal, solver):
+    """Layer-wise PCA on the GPU (one-sided Jacobi on the calibration activations) against the oracle's
+    PCA of the second moment of the same fp16 activations: eigenvalues to 1e-10 of the largest one,
+    eigenvectors of well separated eigenvalues to fp32 resolution, orthogonality, reconstruction --
+    with more rows than channels and with fewer (a null space of any orthonormal completion)."""
+    print(f"case gpu pca full D={D} n_cal={n_cal}", flush=True)
+    lay = synth.make_layer(56, 8, D, 64, n_cal)
+    X16 = lay["X_cal"].astype(np.float16)
+    Qo, lo = O.pca_full(X16, solver)
+    xd = torch.from_numpy(X16).cuda()
+    Qg, lg = B.rosaq_pca_full(xd.data_ptr(), n_cal, D, xd.stride(0))
+    assert np.all(np.diff(lg) <= 0) and np.all(lg >= 0)
+    assert np.max(np.abs(lg - lo)) <= 1e-10 * lo.max()
+    q = Qg.astype(np.float64)
+    assert np.max(np.abs(q.T @ q - np.eye(D))) <= 4e-6
+    big = np.argmax(np.abs(q), axis=0)
+    assert np.all(q[big, np.arange(D)] > 0)                          # sign convention
+    gap = np.minimum(np.abs(np.diff(lo, prepend=np.inf)), np.abs(np.diff(lo, append=-np.inf)))
+    ok = gap > 1e-5 * lo[0]
+    assert ok.sum() >= min(n_cal, D) // 4
+    d = np.minimum(np.abs(q - Qo).max(axis=0), np.abs(q + Qo).max(axis=0))
+    assert np.max(d[ok]) <= 5e-6, np.max(d[ok])
+    C = O.second_moment(X16)
+    assert np.linalg.norm(q @ np.diag(lg) @ q.T - C) <= 1e-5 * np.linalg.norm(C)
+    # the rotated calibration set has a diagonal second moment (Eq. 4)
+    R = O.second_moment(X16.astype(np.float64) @ q)
+    assert np.linalg.norm(R - np.diag(np.diag(R))) <= 1e-5 * np.linalg.norm(C)
+    # the GPU rotation drives the rest of the pipeline like any other Q, lambda
+    ref = O.pack(lay["W"], Qg, lg, 128, 4, O.MODE_FULL)
+    p = B.rosaq_pack_weights(lay["W"], Qg, lg, 128, 4, B.Q_FULL)
+    check_pack(p, ref)
+    check_output(run_gpu(p, lay["x"]), lay["x"], Qg, ref)
+    p.free()
