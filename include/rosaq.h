@@ -204,12 +204,14 @@ int rosaq_packed_export(const rosaq_packed_t* p, int32_t* salient_idx, uint16_t*
                         uint8_t* codes, uint16_t* scales, uint16_t* zeros);
 
 /* rosaq_pca_headwise - calibration step of the method on the GPU (Sec. 3.1 Eq. 4 applied per
- * attention head, Sec. 3.1.1): for every block of 128 input channels the uncentred second
- * moment C_h = X_h^T X_h / n_cal is accumulated in fp64 and diagonalised by cyclic Jacobi
- * rotations (off-diagonal norm <= 1e-13 ||C_h||_F).  Results, ready for rosaq_pack_weights:
+ * attention head, Sec. 3.1.1): for every block of 128 input channels the eigenvectors of the
+ * uncentred second moment C_h = X_h^T X_h / n_cal, found as the right singular vectors of X_h by
+ * one-sided Jacobi rotations in fp64 (pairs of columns are rotated until all are mutually orthogonal;
+ * C_h is never formed; eigenvalue c = |column c of X_h V|^2 / n_cal), until the off-diagonal norm of
+ * the implied C_h is <= 1e-13 ||C_h||_F in every head.  Results, ready for rosaq_pack_weights:
  *   Q_host            HOST fp32 [D/128][128][128], eigenvectors as columns, sorted by eigenvalue
  *                     (descending; each column signed so that its largest entry is positive)
- *   eigenvalues_host  HOST fp64 [D], descending inside every head, negative round-off clamped to 0
+ *   eigenvalues_host  HOST fp64 [D], descending inside every head, >= 0
  *   X_dev             DEVICE fp16 [n_cal x D] calibration activations, row r at X + r*ldx
  * Allocates its own device scratch and waits for the result (calibration time, not the hot path).
  * Errors: NULL, SHAPE, ALIGN, HIP, NOCONVERGE (tolerance not reached within 60 sweeps). */

@@ -150,8 +150,10 @@ static int pack_device(const rosaq_pack_desc& d, hipStream_t st, rosaq_packed* p
   char* tmp = nullptr;
   ROSAQ_HIP(hipMalloc(reinterpret_cast<void**>(&tmp), tmp_total));
   unsigned flag = 0;
-  hipError_t e = hipMemcpy2DAsync(tmp + offs[0], D * 2, d.W, static_cast<size_t>(d.ldw) * 2, D * 2, N,
-                                  hipMemcpyHostToDevice, st);
+  hipError_t e = static_cast<size_t>(d.ldw) == D
+                     ? hipMemcpyAsync(tmp + offs[0], d.W, N * D * 2, hipMemcpyHostToDevice, st)
+                     : hipMemcpy2DAsync(tmp + offs[0], D * 2, d.W, static_cast<size_t>(d.ldw) * 2, D * 2, N,
+                                        hipMemcpyHostToDevice, st);
   if (e == hipSuccess && rotate) e = hipMemcpyAsync(tmp + offs[2], d.Q, q_bytes, hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipMemcpyAsync(d_perm, c.perm.data(), D * 4, hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipMemcpyAsync(d_pos, c.pos.data(), D * 4, hipMemcpyHostToDevice, st);
