@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "librosaq.so")
 HOST_SOURCES = ["rosaq_pack.cpp", "rosaq_api.cpp"]
-HIP_SOURCES = ["rosaq_kernels.hip", "rosaq_pca.hip", "rosaq_static.hip", "rosaq_quant.hip"]
+HIP_SOURCES = ["rosaq_kernels.hip", "rosaq_pca.hip", "rosaq_static.hip", "rosaq_quant.hip", "rosaq_rotate.hip"]
 
 
 def hipcc() -> str:

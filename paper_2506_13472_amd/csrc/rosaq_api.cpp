@@ -259,6 +259,16 @@ static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_
     return launch_gather(x_dev, ldx, M, c.D, p->d_perm, ws + w.xf_a, tickets, n_tickets, hip_stream);
   // xhat = x fp16(Q): a dense fp16 contraction, run as an all-fp16 layer whose
   // "weight" is Q^T with rows already in storage order
+  // 17 to 64 rows: slabs of the contraction, when the caller's workspace has room for their
+  // partial tiles (rosaq_tune("rot_splits", 1) keeps the single launch; measured at 4096^2:
+  // 17.3 against 18.5 us at 64 rows, but 16.2 against 12.8 at 16 rows and 15.5 against 10.1 at
+  // one row, where the single launch pulls few rows of x per compute unit anyway)
+  if (M > 16 && M <= kMBlock && g_tune_rot.splits != 1) {
+    const int slabs = pick_rotate_slabs(c.D, g_tune_rot.splits);
+    if (slabs >= 1 && ws_bytes >= w.part + rotate_slab_part_bytes(c.D, slabs))
+      return launch_rotate_slabs(x_dev, ldx, M, c.D, p->d_qf, slabs, ws + w.part, ws + w.xf_b, tickets,
+                                 n_tickets, hip_stream);
+  }
   GemmArgs a{};
   a.xf = ws + w.xf_a;
   if (M <= 16) {

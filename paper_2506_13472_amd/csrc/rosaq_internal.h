@@ -105,6 +105,15 @@ int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void*
                            const int32_t* pos_dev, void* xf, void* zero_ptr, int zero_count,
                            void* stream);
 
+// Dense rotation of up to 64 rows as slabs of the contraction plus a summing launch
+// (rosaq_rotate.hip).  pick_rotate_slabs: slab count for a D x D rotation (`forced` > 0 asks for
+// that count), 0 = no cut fits; `part` needs rotate_slab_part_bytes(D, slabs) bytes.  The first
+// launch also clears `zero_count` 32-bit words at `zero_ptr`.
+int pick_rotate_slabs(int D, int forced);
+size_t rotate_slab_part_bytes(int D, int slabs);
+int launch_rotate_slabs(const void* x, int64_t ldx, int M, int D, const void* qf, int slabs, void* part,
+                        void* xf_out, void* zero_ptr, int zero_count, void* stream);
+
 int launch_rotate_weights_f64(const void* W_dev, const void* Q_dev, void* out_dev, int N, int D,
                               int headwise, void* stream);
 int launch_stream_probe(const void* src, const void* shared, int workgroups, int threads, int w_kib,

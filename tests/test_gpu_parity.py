@@ -496,13 +496,38 @@ def test_dense_rotation_with_48_channel_tiles(rot_mt):
     ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_FULL)
     p = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_FULL)
     y_default = run_gpu(p, lay["x"])
-    B.rosaq_tune("rot_mt", rot_mt); B.rosaq_tune("rot_nt", 3)
+    B.rosaq_tune("rot_mt", rot_mt); B.rosaq_tune("rot_nt", 3); B.rosaq_tune("rot_splits", 1)
     try:
         y = run_gpu(p, lay["x"])
     finally:
-        B.rosaq_tune("rot_mt", 0); B.rosaq_tune("rot_nt", 0)
+        B.rosaq_tune("rot_mt", 0); B.rosaq_tune("rot_nt", 0); B.rosaq_tune("rot_splits", 0)
     check_output(y, lay["x"], Q, ref)
     check_output(y_default, lay["x"], Q, ref)
+    p.free()
+
+
+@pytest.mark.parametrize("M,D,slabs", [(64, 1024, 0), (17, 1024, 3), (50, 640, 0), (33, 640, 7), (64, 2048, 2),
+                                       (48, 384, 12)])
+def test_dense_rotation_as_slabs_of_the_contraction(M, D, slabs):
+    """Calls of 17 to 64 rows rotate through slabs of the contraction and a summing launch: default
+    and forced slab counts (ragged slabs, a slab of one k-step, 16 and 32 k-steps per slab) against
+    the oracle, against the single-launch rotation, and twice for bit-identical results."""
+    print(f"case slab rotation M={M} D={D} slabs={slabs}", flush=True)
+    lay, Q, lam = make_case(67, M, D, 136, 300, O.MODE_FULL)
+    ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_FULL)
+    p = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_FULL)
+    B.rosaq_tune("rot_splits", 1)
+    try:
+        y_single = run_gpu(p, lay["x"])
+        B.rosaq_tune("rot_splits", slabs)
+        y = run_gpu(p, lay["x"])
+        y_again = run_gpu(p, lay["x"])
+    finally:
+        B.rosaq_tune("rot_splits", 0)
+    check_output(y, lay["x"], Q, ref)
+    assert np.array_equal(y.view(np.uint16), y_again.view(np.uint16))
+    # the two routes add the same fp32 products in different orders
+    assert np.linalg.norm(y.astype(np.float64) - y_single) <= 1e-3 * np.linalg.norm(y_single.astype(np.float64))
     p.free()
 
 
