@@ -259,10 +259,9 @@ int rosaq_stream_probe(const void* src_dev, size_t src_bytes, const void* shared
  *             what the chosen tile fits without spilling)
  *   "splits"  workgroups sharing one output tile of the main GEMM, each over its own part of the
  *             contraction (0 = heuristic, 1 = never split, 2-16; calls of up to 64 rows only)
- *   "rot_splits"  the same for the dense rotation: for calls of 17 to 64 rows the number of slabs
- *             of the contraction whose partial tiles a second launch adds (0 = heuristic, 1 = the
- *             single-launch rotation, 2-16; a count whose slabs exceed 32 k-steps falls back to
- *             the single launch)
+ *   "rot_splits"  the dense rotation of calls of 17 to 64 rows as n = 2-16 slabs of the contraction
+ *             whose partial tiles a second launch adds (0, 1 = the single-launch rotation, the
+ *             default; a count whose slabs exceed 32 k-steps also keeps the single launch)
  *   "stages"  3 = whole call (default), 1 = prologue kernels only, 2 = main GEMM only
  *             (2 reuses the rotated activations a previous call left in the workspace)
  * For benchmarks and tests only: the settings are process-wide and not synchronised, so no other

@@ -257,18 +257,19 @@ static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_
                                   hip_stream);
   if (c.q_mode == ROSAQ_Q_NONE)
     return launch_gather(x_dev, ldx, M, c.D, p->d_perm, ws + w.xf_a, tickets, n_tickets, hip_stream);
-  // xhat = x fp16(Q): a dense fp16 contraction, run as an all-fp16 layer whose
-  // "weight" is Q^T with rows already in storage order
-  // 17 to 64 rows: slabs of the contraction, when the caller's workspace has room for their
-  // partial tiles (rosaq_tune("rot_splits", 1) keeps the single launch; measured at 4096^2:
-  // 17.3 against 18.5 us at 64 rows, but 16.2 against 12.8 at 16 rows and 15.5 against 10.1 at
-  // one row, where the single launch pulls few rows of x per compute unit anyway)
-  if (M > 16 && M <= kMBlock && g_tune_rot.splits != 1) {
+  // xhat = x fp16(Q), a dense fp16 contraction.
+  // rosaq_tune("rot_splits", n >= 2), 17 to 64 rows: slabs of the contraction and a summing launch,
+  // when the caller's workspace has room for the partial tiles.  Not the default: measured at
+  // 4096^2 and 64 rows, a stream of single calls gains 6 % (17.3 against 18.5 us) but a whole decode
+  // step, where other launches sit between the rotations, loses 0.2 % (3.125 against 3.118 ms).
+  if (M > 16 && M <= kMBlock && g_tune_rot.splits >= 2) {
     const int slabs = pick_rotate_slabs(c.D, g_tune_rot.splits);
     if (slabs >= 1 && ws_bytes >= w.part + rotate_slab_part_bytes(c.D, slabs))
       return launch_rotate_slabs(x_dev, ldx, M, c.D, p->d_qf, slabs, ws + w.part, ws + w.xf_b, tickets,
                                  n_tickets, hip_stream);
   }
+  // the default: one launch of the all-fp16 GEMM whose "weight" is Q^T with rows already in
+  // storage order
   GemmArgs a{};
   a.xf = ws + w.xf_a;
   if (M <= 16) {
@@ -280,8 +281,6 @@ static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_
   } else {
     const int rc = launch_gather(x_dev, ldx, M, c.D, nullptr, ws + w.xf_a, tickets, n_tickets, hip_stream);
     if (rc != ROSAQ_OK) return rc;
-    a.part = ws + w.part; a.part_bytes = ws_bytes > w.part ? ws_bytes - w.part : 0;
-    a.tickets = tickets; a.ticket_count = kTicketsPerLaunch;
   }
   a.nseg = 1;
   a.seg[0].wS = p->d_qf; a.seg[0].wq = nullptr;
@@ -289,7 +288,9 @@ static int run_prologue(const rosaq_packed_t* p, const WsPlan& w, const void* x_
   a.M = M;
   a.ks_s = c.D / kKStep; a.G = 0; a.KS = c.D / kKStep; a.KS_out = c.D / kKStep;
   a.bits = 4; a.out_frag = 1;
-  return launch_gemm(a, g_tune_rot, hip_stream);
+  GemmTune tune = g_tune_rot;
+  tune.splits = 1;           // "rot_splits" selects the slab launches above, never a ticketed split
+  return launch_gemm(a, tune, hip_stream);
 }
 
 static int run_call(const rosaq_packed_t* const* ps, int count, const void* x_dev, int M,

@@ -106,9 +106,9 @@ int launch_rotate_headwise(const void* x, int64_t ldx, int M, int D, const void*
                            void* stream);
 
 // Dense rotation of up to 64 rows as slabs of the contraction plus a summing launch
-// (rosaq_rotate.hip).  pick_rotate_slabs: slab count for a D x D rotation (`forced` > 0 asks for
-// that count), 0 = no cut fits; `part` needs rotate_slab_part_bytes(D, slabs) bytes.  The first
-// launch also clears `zero_count` 32-bit words at `zero_ptr`.
+// (rosaq_rotate.hip).  pick_rotate_slabs: `forced` if slabs of that count fit the kernel, else 0;
+// `part` needs rotate_slab_part_bytes(D, slabs) bytes.  The first launch also clears `zero_count`
+// 32-bit words at `zero_ptr`.
 int pick_rotate_slabs(int D, int forced);
 size_t rotate_slab_part_bytes(int D, int slabs);
 int launch_rotate_slabs(const void* x, int64_t ldx, int M, int D, const void* qf, int slabs, void* part,

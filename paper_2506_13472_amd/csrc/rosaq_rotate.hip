@@ -2,6 +2,7 @@
 // rotation of Sec. 3.1): a skinny fp16 contraction whose cost is the stream of fp16(Q) from HBM
 // (2 D^2 bytes: 33.5 MB at D = 4096, 52 MB at D = 5120).
 //
+// An alternative to the single output-stationary launch, selected with rosaq_tune("rot_splits", n).
 // Two launches, no workgroup waits for another and nothing is exchanged inside a launch:
 //   rotate_slab_kernel  one workgroup owns a slab of the contraction (a run of k-steps) and a
 //                       chunk of eight 16-channel tiles.  Its slab of x (all rows) is read once,
@@ -159,20 +160,12 @@ static int rot_fail(hipError_t e, const char* what) {
   return ROSAQ_ERR_HIP;
 }
 
-// Slabs of a D x D rotation: one round of workgroups (D / 128 chunks x slabs <= 256, as many as
-// possible) whose slab fits the LDS (32 k-steps).  0 when no such cut exists (large D: the
-// output-stationary launch already streams well).  `forced` > 0 asks for that count.
+// Checks a slab count for a D x D rotation: every slab must fit the LDS (32 k-steps).  Returns the
+// count, or 0 when it does not fit (the caller then keeps the single launch).
 int pick_rotate_slabs(int D, int forced) {
-  const int KS = D / kKStep, chunks = D / 128;
-  int best = 0, best_wgs = 0;
-  for (int s = 1; s <= kMaxSplits && s <= KS; ++s) {
-    if (forced > 0 && s != forced) continue;
-    if ((KS + s - 1) / s > 32) continue;
-    const int wgs = chunks * s;
-    if (wgs > 256 && forced <= 0) break;
-    if (wgs > best_wgs) { best = s; best_wgs = wgs; }
-  }
-  return best;
+  const int KS = D / kKStep;
+  if (forced < 1 || forced > kMaxSplits || forced > KS) return 0;
+  return (KS + forced - 1) / forced <= 32 ? forced : 0;
 }
 
 size_t rotate_slab_part_bytes(int D, int slabs) {

@@ -506,12 +506,12 @@ def test_dense_rotation_with_48_channel_tiles(rot_mt):
     p.free()
 
 
-@pytest.mark.parametrize("M,D,slabs", [(64, 1024, 0), (17, 1024, 3), (50, 640, 0), (33, 640, 7), (64, 2048, 2),
-                                       (48, 384, 12)])
+@pytest.mark.parametrize("M,D,slabs", [(64, 1024, 8), (17, 1024, 3), (50, 640, 16), (33, 640, 7), (64, 2048, 2),
+                                       (48, 384, 12), (64, 2048, 4)])
 def test_dense_rotation_as_slabs_of_the_contraction(M, D, slabs):
-    """Calls of 17 to 64 rows rotate through slabs of the contraction and a summing launch: default
-    and forced slab counts (ragged slabs, a slab of one k-step, 16 and 32 k-steps per slab) against
-    the oracle, against the single-launch rotation, and twice for bit-identical results."""
+    """The alternative rotation of calls of 17 to 64 rows through slabs of the contraction and a
+    summing launch (ragged slabs, a slab of one k-step, 16 and 32 k-steps per slab): against the
+    oracle, against the single-launch rotation, and twice for bit-identical results."""
     print(f"case slab rotation M={M} D={D} slabs={slabs}", flush=True)
     lay, Q, lam = make_case(67, M, D, 136, 300, O.MODE_FULL)
     ref = O.pack(lay["W"], Q, lam, 128, 4, O.MODE_FULL)

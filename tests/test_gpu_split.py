@@ -53,7 +53,7 @@ def test_split_launch_matches_oracle(splits, M, nt):
 
 @pytest.mark.parametrize("mode,bits", [(O.MODE_NONE, 3), (O.MODE_FULL, 4)])
 def test_split_launch_other_modes_and_dense_rotation_split(mode, bits):
-    """INT3 without rotation, and a dense rotation whose own GEMM launch is split too."""
+    """INT3 without rotation, and a dense rotation that runs as two slabs of its contraction."""
     print(f"case split mode={mode} bits={bits}", flush=True)
     lay, Q, lam = make_case(32, 48, 512, 160, 300, mode)
     ref = O.pack(lay["W"], Q, lam, 128, bits, mode)
