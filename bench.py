@@ -384,7 +384,7 @@ def main():
     ap.add_argument("--depth", type=int, default=0, help="tuning aid: units in flight per wave (2-4)")
     ap.add_argument("--splits", type=int, default=0, help="tuning aid: workgroups per output tile (1-16)")
     ap.add_argument("--rot", default="", help="tuning aid: mt,nt,depth of the dense-rotation launch")
-    ap.add_argument("--rot-splits", type=int, default=0, help="tuning aid: workgroups per tile of the dense rotation")
+    ap.add_argument("--rot-splits", type=int, default=0, help="tuning aid: slabs of the contraction for the dense rotation of 17-64 rows (2-16)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
