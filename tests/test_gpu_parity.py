@@ -288,7 +288,7 @@ def test_headwise_device_rotation_packs_the_same_bits_as_the_host_path():
 
 @pytest.mark.parametrize("D,n_cal", [(256, 512), (1024, 700)])
 def test_pca_headwise_on_gpu_against_oracle(D, n_cal):
-    """Calibration on the GPU (second moment + Jacobi per head) against the oracle's PCA of the
+    """Calibration on the GPU (one-sided Jacobi per head) against the oracle's PCA of the
     same fp16 activations: eigenvalues to 1e-10, eigenvectors to fp32 resolution, orthogonality,
     and the packed layer built from the GPU rotation equals the one built from the oracle's."""
     print(f"case gpu pca D={D}", flush=True)
