@@ -143,6 +143,9 @@ static int pack_device(const rosaq_pack_desc& d, hipStream_t st, rosaq_packed* p
   p->d_perm = static_cast<int32_t*>(d_perm);
   p->d_pos = static_cast<int32_t*>(d_pos);
 
+  // host arrays the canonical form comes back into (sized before the scratch exists: an allocation
+  // failure here must not leave it behind)
+  c.W_S.resize(N * K); c.codes.resize(N * C); c.scales.resize(N * G); c.zeros.resize(N * G);
   // scratch of this call: [W | What | Q | W_S | codes | scales | zeros | flag]
   const size_t sizes[] = {N * D * 2, rotate ? N * D * 2 : 0, q_bytes, N * K * 2, N * C, N * G * 2, N * G * 2, 256};
   size_t offs[8], tmp_total = 0;
@@ -176,7 +179,6 @@ static int pack_device(const rosaq_pack_desc& d, hipStream_t st, rosaq_packed* p
   if (e == hipSuccess && rc == ROSAQ_OK && keep_q)
     rc = launch_rotation_image(tmp + offs[2], c.D, headwise ? 1 : 0, p->d_perm, p->d_qf, st);
   if (e == hipSuccess && rc == ROSAQ_OK) {
-    c.W_S.resize(N * K); c.codes.resize(N * C); c.scales.resize(N * G); c.zeros.resize(N * G);
     if (N * K) e = hipMemcpyAsync(c.W_S.data(), tmp + offs[3], N * K * 2, hipMemcpyDeviceToHost, st);
     if (e == hipSuccess && N * C) e = hipMemcpyAsync(c.codes.data(), tmp + offs[4], N * C, hipMemcpyDeviceToHost, st);
     if (e == hipSuccess && N * G) e = hipMemcpyAsync(c.scales.data(), tmp + offs[5], N * G * 2, hipMemcpyDeviceToHost, st);
@@ -512,7 +514,9 @@ int rosaq_pca_headwise(const void* X_dev, int32_t n_cal, int32_t D, int64_t ldx,
   if (n_cal < 1 || D < kHeadDim || D % kHeadDim != 0 || ldx < D)
     return fail(ROSAQ_ERR_SHAPE, "n_cal >= 1, D a positive multiple of 128, ldx >= D");
   if (reinterpret_cast<uintptr_t>(X_dev) % 2) return fail(ROSAQ_ERR_ALIGN, "X must be 2-byte aligned");
-  return pca_headwise_device(X_dev, n_cal, D, ldx, Q_host, eigenvalues_host, hip_stream);
+  try {   // the solver keeps host-side bookkeeping in vectors
+    return pca_headwise_device(X_dev, n_cal, D, ldx, Q_host, eigenvalues_host, hip_stream);
+  } catch (const std::exception&) { return fail(ROSAQ_ERR_NOMEM, "out of host memory"); }
 }
 
 int rosaq_pca_full(const void* X_dev, int32_t n_cal, int32_t D, int64_t ldx, float* Q_host,
@@ -521,7 +525,9 @@ int rosaq_pca_full(const void* X_dev, int32_t n_cal, int32_t D, int64_t ldx, flo
   if (n_cal < 1 || D < kGroup || D % kGroup != 0 || D > 8192 || ldx < D)
     return fail(ROSAQ_ERR_SHAPE, "n_cal >= 1, D a multiple of 128 up to 8192, ldx >= D");
   if (reinterpret_cast<uintptr_t>(X_dev) % 2) return fail(ROSAQ_ERR_ALIGN, "X must be 2-byte aligned");
-  return pca_full_device(X_dev, n_cal, D, ldx, Q_host, eigenvalues_host, hip_stream);
+  try {
+    return pca_full_device(X_dev, n_cal, D, ldx, Q_host, eigenvalues_host, hip_stream);
+  } catch (const std::exception&) { return fail(ROSAQ_ERR_NOMEM, "out of host memory"); }
 }
 
 int rosaq_stream_probe(const void* src_dev, size_t src_bytes, const void* shared_dev,

@@ -140,6 +140,9 @@ static int pca_blocks_device(const void* X_dev, int n_cal, int D, int Db, int64_
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int n_pad = (n_cal + 3) / 4 * 4, blocks = D / Db, half = Db / 2, rounds = Db - 1;
   const int seats = blocks * half;
+  // host bookkeeping first: if it cannot be had, nothing on the device has been allocated yet
+  std::vector<double> stats(static_cast<size_t>(blocks) * 2), V, lam(D);
+  std::vector<int> order(Db);
   double *dY = nullptr, *dV = nullptr, *dG = nullptr, *dD = nullptr, *dS = nullptr, *dL = nullptr;
   hipError_t e = hipMalloc(&dY, static_cast<size_t>(D) * n_pad * 8);
   if (e == hipSuccess) e = hipMalloc(&dV, static_cast<size_t>(D) * Db * 8);
@@ -150,7 +153,6 @@ static int pca_blocks_device(const void* X_dev, int n_cal, int D, int Db, int64_
   constexpr int kMaxSweeps = 60;
   constexpr double kTol = 1e-13;
   bool converged = false;
-  std::vector<double> stats(static_cast<size_t>(blocks) * 2);
   if (e == hipSuccess) {
     hipLaunchKernelGGL(hestenes_init_kernel, dim3(D), dim3(256), 0, st, static_cast<const _Float16*>(X_dev), ldx,
                        n_cal, n_pad, Db, dY, dV);
@@ -176,7 +178,6 @@ static int pca_blocks_device(const void* X_dev, int n_cal, int D, int Db, int64_
       if (!(off2 <= kTol * kTol * norm2)) converged = false;
     }
   }
-  std::vector<double> V, lam(D);
   if (e == hipSuccess) {
     hipLaunchKernelGGL(hestenes_norms_kernel, dim3(D), dim3(256), 0, st, dY, n_pad, n_cal, dL);
     e = hipGetLastError();
@@ -194,7 +195,6 @@ static int pca_blocks_device(const void* X_dev, int n_cal, int D, int Db, int64_
     set_error("one-sided Jacobi did not converge within 60 sweeps");
     return ROSAQ_ERR_NOCONVERGE;
   }
-  std::vector<int> order(Db);
   for (int b = 0; b < blocks; ++b) {
     const double* lb = &lam[static_cast<size_t>(b) * Db];
     std::iota(order.begin(), order.end(), 0);
