@@ -328,8 +328,12 @@ void gemm_kernel(GemmDev p) {
 
   // Per-wave work list: fp16 k-steps u = wave, wave + WPB, ... and low-bit groups
   // g = g_first, g_first + WPB, ... (unit ks_s + g belongs to wave (ks_s + g) % WPB).
-  // Loads run two units ahead of the MFMAs; everything a wave needs first is
-  // requested before it waits for anything, in the order it will be consumed.
+  // DEPTH units are requested ahead of the one being multiplied, and everything a wave needs
+  // first is requested before it waits for anything.  How much of that overlaps inside a wave
+  // is up to the compiler's wait placement (with the refills under conditions, as here, the first
+  // use of a unit waits for every load in flight); a variant with exact progressive waits was
+  // measured and was not faster: the launch is bound by what the L1 / L2 path delivers per
+  // compute unit, and latency is covered by the other waves.
   struct StepRegs {
     uint4 a[MT];
     uint4 b[NT];
