@@ -230,12 +230,15 @@ def shape_sweep(torch, shapes, ms_override, reps, emit):
         del W16, w16
 
 
-def decode_workload(torch, steps, warmup, absorbed=False):
+def decode_workload(torch, steps, warmup, absorbed=False, chained_mlp=True):
     """The linears of a LLaMA-7B-shaped decode step at batch 64, INT4 g128, K = 128: per layer
     q/k/v (one batched call, shared head-wise rotation), o (head-wise), gate/up (one batched call
     sharing one dense 4096 x 4096 rotation) and down (no rotation, the paper's setting for W_D);
-    32 layers per step, every layer its own device copy of weights and rotations.  Returns a dict with
-    the time per step next to the same linears as fp16 torch.matmul calls."""
+    32 layers per step, every layer its own device copy of weights and rotations.  With `chained_mlp`
+    the three FFN linears are one rosaq_mlp_swiglu call (the gated product goes straight into the down
+    projection's input fragments); without it, rosaq_linear_swiglu and rosaq_linear(down) on a buffer
+    of the same shape.  Returns a dict with the time per step next to the same linears as fp16
+    torch.matmul calls."""
     from paper_2506_13472_amd import binding as B, synth, torch_glue as T
     dev = torch.device("cuda:0")
     timer = Timer(torch, torch.cuda.Stream())
@@ -266,7 +269,8 @@ def decode_workload(torch, steps, warmup, absorbed=False):
     y_f = [torch.empty((M, f), dtype=torch.float16, device=dev) for _ in range(2)]
     ws_bytes = max([B.rosaq_workspace_bytes(h, M) for h in base.values()] +
                    [B.rosaq_workspace_bytes_batch([base[n] for n in "qkv"], M),
-                    B.rosaq_workspace_bytes_batch([base["gate"], base["up"]], M)])
+                    B.rosaq_workspace_bytes_batch([base["gate"], base["up"]], M),
+                    B.rosaq_workspace_bytes_mlp(base["gate"], base["up"], base["down"], M)])
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     qkv = [B.BatchArgs([lay[n] for n in "qkv"], [y.data_ptr() for y in y_d[:3]], [y.stride(0) for y in y_d[:3]])
            for lay in layers]
@@ -276,10 +280,15 @@ def decode_workload(torch, steps, warmup, absorbed=False):
         for l, lay in enumerate(layers):
             B.rosaq_linear_batch(qkv[l], x.data_ptr(), M, x.stride(0), ws.data_ptr(), ws.numel(), sp)
             T.linear(lay["o"], x, y_d[3], ws)
-            # gate and up in one launch, silu(gate) * up applied in its epilogue
-            B.rosaq_linear_swiglu(lay["gate"], lay["up"], x.data_ptr(), M, x.stride(0), y_f[0].data_ptr(),
-                                  y_f[0].stride(0), ws.data_ptr(), ws.numel(), sp)
-            T.linear(lay["down"], xh, y_d[3], ws)
+            if chained_mlp:
+                # gate and up in one launch, silu(gate) * up applied in its epilogue and written as the
+                # down projection's input fragments; then the down projection
+                B.rosaq_mlp_swiglu(lay["gate"], lay["up"], lay["down"], x.data_ptr(), M, x.stride(0),
+                                   y_d[3].data_ptr(), y_d[3].stride(0), ws.data_ptr(), ws.numel(), sp)
+            else:
+                B.rosaq_linear_swiglu(lay["gate"], lay["up"], x.data_ptr(), M, x.stride(0), y_f[0].data_ptr(),
+                                      y_f[0].stride(0), ws.data_ptr(), ws.numel(), sp)
+                T.linear(lay["down"], xh, y_d[3], ws)
 
     # fp16: the same seven linears per layer as separate vendor GEMMs, and with q/k/v and gate/up fused
     W_qkv = [torch.randn((3 * d, d), dtype=torch.float16, device=dev) * 0.02 for _ in range(L)]
@@ -317,14 +326,15 @@ def decode_workload(torch, steps, warmup, absorbed=False):
                  + 2 * M * (4 * d + 4 * d) + 2 * M * (d + f) + 2 * M * (f + d))      # x and y of the four calls
     fp16_layer = 2 * (4 * d * d + 3 * d * f) + 2 * M * (2 * d + 4 * d) + 2 * M * (d + 2 * f) + 2 * M * (f + d)
     ms = t["median"]
+    ffn = ("rosaq_mlp_swiglu(gate,up,down; silu(gate)*up written as down's input fragments)" if chained_mlp else
+           "rosaq_linear_swiglu(gate,up; silu(gate)*up in the epilogue) + rosaq_linear(down)")
     out = {
         "workload": "llama7b_decode_linears_M64_int4" + ("_rotations_absorbed" if ab else ""),
         "layers": L, "linears_per_step": 7 * L, "M": M,
-        "calls_per_layer": ("rosaq_linear_batch(q,k,v) + rosaq_linear(o) + rosaq_linear_swiglu(gate,up) + "
-                            "rosaq_linear(down): inputs arrive rotated, run time only permutes them") if ab else
-                           ("rosaq_linear_batch(q,k,v; head-wise) + rosaq_linear_headwise(o) + "
-                            "rosaq_linear_swiglu(gate,up; dense 4096^2 rotation, silu(gate)*up in the epilogue) + "
-                            "rosaq_linear(down; no rotation)"),
+        "calls_per_layer": (("rosaq_linear_batch(q,k,v) + rosaq_linear(o) + " + ffn +
+                             ": inputs arrive rotated, run time only permutes them") if ab else
+                            ("rosaq_linear_batch(q,k,v; head-wise) + rosaq_linear_headwise(o) + " + ffn +
+                             "; gate/up behind one dense 4096^2 rotation, down without rotation")),
         "steps_timed": steps, "ms_per_step": round(ms, 4), "ms_per_step_p10": round(t["p10"], 4),
         "ms_per_step_p90": round(t["p90"], 4), "total_s": round(ms * steps * 1e-3, 4),
         "tokens_per_s": round(M / (ms * 1e-3), 1),
@@ -373,6 +383,8 @@ def main():
     ap.add_argument("--absorbed", action="store_true",
                     help="with --decode: pack every layer with rotation_absorbed (the paper's deployment: "
                          "rotations folded into the producing layers offline, no rotation at run time)")
+    ap.add_argument("--unchained-mlp", action="store_true",
+                    help="with --decode: rosaq_linear_swiglu + rosaq_linear(down) instead of rosaq_mlp_swiglu")
     ap.add_argument("--sweep-filter", default="", help="substring of the shape names to run")
     ap.add_argument("--sweep-m", default="", help="comma-separated M values replacing each shape's own list")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -418,7 +430,7 @@ def main():
         shape_sweep(torch, shapes, ms, 20, lambda row: print(json.dumps(row), flush=True))
         return
     if args.decode:
-        print(json.dumps(decode_workload(torch, args.decode_steps, args.warmup, args.absorbed)), flush=True)
+        print(json.dumps(decode_workload(torch, args.decode_steps, args.warmup, args.absorbed, not args.unchained_mlp)), flush=True)
         return
 
     # ---- synthetic layers: calibrate (PCA per head on the GPU), pack, all through the C ABI ------

@@ -188,6 +188,28 @@ int rosaq_linear_swiglu(const rosaq_packed_t* gate, const rosaq_packed_t* up, co
                         int64_t ldx, void* y_dev, int64_t ldy, void* ws_dev, size_t ws_bytes,
                         void* hip_stream);
 
+/* rosaq_mlp_swiglu - the gated FFN block of a decoder layer in three launches:
+ *     y = h What_down^T,   h = silu(xhat What_gate^T) * (xhat What_up^T)   (rosaq_linear_swiglu),
+ * for a down projection that needs no rotation at run time (packed with q_mode NONE, the paper's
+ * setting for W_D, or with rotation_absorbed).  The gated product is rounded to fp16 once and
+ * written straight into the down projection's input fragments, each channel at the storage
+ * position that layer's salient-channel split assigns it (Sec. 3.2), so h never exists in
+ * row-major form and no permutation launch runs in front of the down projection.  The result
+ * equals, bit for bit, rosaq_linear_swiglu followed by rosaq_linear(down).
+ *   gate, up  as for rosaq_linear_swiglu
+ *   down      handle with in_features = gate's out_features and q_mode NONE at run time
+ *   x_dev     DEVICE fp16 [M x gate.in_features], row stride ldx
+ *   y_dev     DEVICE fp16 [M x down.out_features], row stride ldy
+ *   ws_dev    DEVICE scratch of at least rosaq_workspace_bytes_mlp(gate, up, down, M) bytes
+ *             (256-byte aligned; that size includes room for a split launch of the down projection)
+ * Errors: those of rosaq_linear, MODE (gate / up differ, or down rotates at run time), SHAPE (down's
+ * input width). */
+size_t rosaq_workspace_bytes_mlp(const rosaq_packed_t* gate, const rosaq_packed_t* up,
+                                 const rosaq_packed_t* down, int32_t M);
+int rosaq_mlp_swiglu(const rosaq_packed_t* gate, const rosaq_packed_t* up, const rosaq_packed_t* down,
+                     const void* x_dev, int32_t M, int64_t ldx, void* y_dev, int64_t ldy, void* ws_dev,
+                     size_t ws_bytes, void* hip_stream);
+
 /* Shape and storage facts of a handle (any output pointer may be NULL). */
 int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* K,
                       int32_t* bits, int32_t* group, int32_t* q_mode,

@@ -22,7 +22,7 @@ ERR_NAMES = {0: "OK", -1: "NULL", -2: "SHAPE", -3: "ARG", -4: "MODE", -5: "ALIGN
 LIB_PATH = os.environ.get("ROSAQ_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "librosaq.so")
 
 EXPORTED = ["rosaq_pack_weights", "rosaq_workspace_bytes", "rosaq_workspace_bytes_batch", "rosaq_workspace_bytes_min", "rosaq_linear", "rosaq_linear_headwise",
-            "rosaq_linear_headwise_static", "rosaq_linear_batch", "rosaq_linear_swiglu", "rosaq_stream_probe", "rosaq_packed_clone", "rosaq_pca_headwise", "rosaq_pca_full",
+            "rosaq_linear_headwise_static", "rosaq_linear_batch", "rosaq_linear_swiglu", "rosaq_mlp_swiglu", "rosaq_workspace_bytes_mlp", "rosaq_stream_probe", "rosaq_packed_clone", "rosaq_pca_headwise", "rosaq_pca_full",
             "rosaq_packed_info", "rosaq_packed_export", "rosaq_tune", "rosaq_launch_shape", "rosaq_block_map", "rosaq_packed_image", "rosaq_free",
             "rosaq_last_error"]
 
@@ -80,6 +80,10 @@ def lib() -> C.CDLL:
         L.rosaq_linear_batch.restype = C.c_int
         L.rosaq_linear_swiglu.argtypes = [vp, vp, vp, i32, i64, vp, i64, vp, sz, vp]
         L.rosaq_linear_swiglu.restype = C.c_int
+        L.rosaq_mlp_swiglu.argtypes = [vp, vp, vp, vp, i32, i64, vp, i64, vp, sz, vp]
+        L.rosaq_mlp_swiglu.restype = C.c_int
+        L.rosaq_workspace_bytes_mlp.argtypes = [vp, vp, vp, i32]
+        L.rosaq_workspace_bytes_mlp.restype = sz
         L.rosaq_pca_headwise.argtypes = [vp, i32, i32, i64, vp, vp, vp]
         L.rosaq_pca_headwise.restype = C.c_int
         L.rosaq_pca_full.argtypes = [vp, i32, i32, i64, vp, vp, vp]
@@ -230,6 +234,16 @@ def rosaq_linear_batch(args: BatchArgs, x_ptr: int, M: int, ldx: int, ws_ptr: in
 def rosaq_linear_swiglu(gate: Packed, up: Packed, x_ptr: int, M: int, ldx: int, y_ptr: int, ldy: int,
                         ws_ptr: int, ws_bytes: int, stream: int = 0):
     _check(lib().rosaq_linear_swiglu(gate.handle, up.handle, x_ptr, M, ldx, y_ptr, ldy, ws_ptr, ws_bytes, stream))
+
+
+def rosaq_workspace_bytes_mlp(gate: Packed, up: Packed, down: Packed, M: int) -> int:
+    return lib().rosaq_workspace_bytes_mlp(gate.handle, up.handle, down.handle, M)
+
+
+def rosaq_mlp_swiglu(gate: Packed, up: Packed, down: Packed, x_ptr: int, M: int, ldx: int, y_ptr: int, ldy: int,
+                     ws_ptr: int, ws_bytes: int, stream: int = 0):
+    _check(lib().rosaq_mlp_swiglu(gate.handle, up.handle, down.handle, x_ptr, M, ldx, y_ptr, ldy, ws_ptr,
+                                  ws_bytes, stream))
 
 
 def rosaq_pca_headwise(x_ptr: int, n_cal: int, D: int, ldx: int, stream: int = 0):

@@ -225,13 +225,34 @@ static int check_device(const rosaq_packed_t* const* ps, int count) {
   return ROSAQ_OK;
 }
 
-// y_i = xhat W_i^T for `count` layers that share the xhat fragments in the workspace.
-static int run_main_gemm(const rosaq_packed_t* const* ps, int count, const WsPlan& w, int M,
-                         void* const* ys, const int64_t* ldys, char* ws, size_t ws_bytes, void* stream,
-                         bool swiglu = false) {
+// Buffers of one main-GEMM launch.  `chain_*`: a gated pair that feeds a following layer writes its
+// product as that layer's input fragments (rosaq_mlp_swiglu) and clears that layer's tickets.
+struct GemmIO {
+  const void* xf;            // xhat fragments the launch reads
+  void* tickets;             // kTicketsPerLaunch words, zero before the launch
+  void* part;                // room for partial tiles of a split launch
+  size_t part_bytes;
+  const int32_t* chain_pos = nullptr;   // device: channel -> storage position of the next layer
+  int chain_ks = 0;                     // k-steps of the next layer's input
+  void* zero_ptr = nullptr;
+  int zero_count = 0;
+};
+
+static GemmIO plan_io(const rosaq_packed& p0, const WsPlan& w, char* ws, size_t ws_bytes) {
+  GemmIO io{};
+  io.xf = ws + (p0.c.q_mode == ROSAQ_Q_FULL ? w.xf_b : w.xf_a);
+  io.tickets = ws + w.tickets + kTicketsPerLaunch * sizeof(uint32_t);
+  io.part = ws + w.part;
+  io.part_bytes = ws_bytes > w.part ? ws_bytes - w.part : 0;
+  return io;
+}
+
+// y_i = xhat W_i^T for `count` layers that share the xhat fragments `io.xf`.
+static int run_main_gemm(const rosaq_packed_t* const* ps, int count, const GemmIO& io, int M,
+                         void* const* ys, const int64_t* ldys, void* stream, bool swiglu = false) {
   const Canonical& c = ps[0]->c;
   GemmArgs a{};
-  a.xf = ws + (c.q_mode == ROSAQ_Q_FULL ? w.xf_b : w.xf_a);
+  a.xf = io.xf;
   a.nseg = count;
   for (int i = 0; i < count; ++i) {
     const rosaq_packed_t* p = ps[i];
@@ -241,8 +262,10 @@ static int run_main_gemm(const rosaq_packed_t* const* ps, int count, const WsPla
   a.M = M;
   a.ks_s = c.K / kKStep; a.G = c.G; a.KS = c.D / kKStep; a.KS_out = 0;
   a.bits = c.bits; a.out_frag = 0;
-  a.part = ws + w.part; a.part_bytes = ws_bytes > w.part ? ws_bytes - w.part : 0;
-  a.tickets = ws + w.tickets + kTicketsPerLaunch * sizeof(uint32_t); a.ticket_count = kTicketsPerLaunch;
+  if (io.chain_pos) { a.out_frag = 2; a.out_pos = io.chain_pos; a.KS_out = io.chain_ks; }
+  a.part = io.part; a.part_bytes = io.part_bytes;
+  a.tickets = io.tickets; a.ticket_count = kTicketsPerLaunch;
+  a.zero_ptr = io.zero_ptr; a.zero_count = io.zero_count;
   a.swiglu = swiglu ? 1 : 0;
   return launch_gemm(a, g_tune, stream);
 }
@@ -303,7 +326,7 @@ static int run_call(const rosaq_packed_t* const* ps, int count, const void* x_de
     if (rc != ROSAQ_OK) return rc;
   }
   if (!(g_tune_stages & 2)) return ROSAQ_OK;
-  return run_main_gemm(ps, count, w, M, ys, ldys, ws, ws_bytes, hip_stream, swiglu);
+  return run_main_gemm(ps, count, plan_io(*ps[0], w, ws, ws_bytes), M, ys, ldys, hip_stream, swiglu);
 }
 
 static uint64_t fnv1a(uint64_t h, const void* data, size_t n) {
@@ -481,6 +504,89 @@ int rosaq_linear_swiglu(const rosaq_packed_t* gate, const rosaq_packed_t* up, co
   void* ys[2] = {y_dev, y_dev};
   const int64_t ldys[2] = {ldy, ldy};
   return run_call(ps, 2, x_dev, M, ldx, ys, ldys, static_cast<char*>(ws_dev), ws_bytes, w, hip_stream, true);
+}
+
+// Workspace of rosaq_mlp_swiglu: [gate / up: what rosaq_linear_swiglu needs without room for partial
+// tiles | down: xhat fragments, tickets | room for the down launch's partial tiles].
+struct MlpPlan {
+  WsPlan gate;
+  size_t down_xf = 0, down_tickets = 0, required = 0, part = 0, total = 0;
+};
+static MlpPlan plan_mlp(const rosaq_packed& gate, const rosaq_packed& down, int M) {
+  MlpPlan m;
+  m.gate = plan_workspace(gate, M);
+  const size_t mblocks = (static_cast<size_t>(M) + kMBlock - 1) / kMBlock;
+  size_t off = m.gate.required;
+  m.down_xf = off; off += align_up(mblocks * (down.c.D / kKStep) * 4 * 64 * 16, 256);
+  m.down_tickets = off; off += kTicketBytes;
+  m.required = off;
+  m.part = off;
+  off += align_up(part_room(M, down.c.N), 256);
+  m.total = off;
+  return m;
+}
+
+static int check_mlp(const rosaq_packed_t* gate, const rosaq_packed_t* up, const rosaq_packed_t* down) {
+  if (!gate || !up || !down) return fail(ROSAQ_ERR_NULL, "a layer handle is NULL");
+  const Canonical &a = gate->c, &b = up->c, &d = down->c;
+  if (a.N != b.N || a.D != b.D || a.K != b.K || a.bits != b.bits || a.q_mode != b.q_mode ||
+      gate->rot_fingerprint != up->rot_fingerprint)
+    return fail(ROSAQ_ERR_MODE, "gate and up must share N, D, K, bits and the rotation");
+  if (d.D != a.N) return fail(ROSAQ_ERR_SHAPE, "down must take gate's output channels as its input");
+  if (d.q_mode != ROSAQ_Q_NONE)
+    return fail(ROSAQ_ERR_MODE, "down must run without a run-time rotation (q_mode NONE or rotation_absorbed)");
+  return ROSAQ_OK;
+}
+
+size_t rosaq_workspace_bytes_mlp(const rosaq_packed_t* gate, const rosaq_packed_t* up,
+                                 const rosaq_packed_t* down, int32_t M) {
+  if (check_mlp(gate, up, down) != ROSAQ_OK || M < 1) return 0;
+  return plan_mlp(*gate, *down, M).total;
+}
+
+int rosaq_mlp_swiglu(const rosaq_packed_t* gate, const rosaq_packed_t* up, const rosaq_packed_t* down,
+                     const void* x_dev, int32_t M, int64_t ldx, void* y_dev, int64_t ldy, void* ws_dev,
+                     size_t ws_bytes, void* hip_stream) {
+  int rc = check_mlp(gate, up, down);
+  if (rc != ROSAQ_OK) return rc;
+  // x against gate, y against down; the workspace is checked against this call's own plan below
+  WsPlan unused;
+  const bool headwise = gate->c.q_mode == ROSAQ_Q_HEADWISE;
+  char* ws = static_cast<char*>(ws_dev);
+  rc = check_call(gate, x_dev, M, ldx, y_dev, gate->c.N, ws_dev, ws_bytes, headwise, &unused);
+  if (rc != ROSAQ_OK) return rc;
+  if (!y_dev) return fail(ROSAQ_ERR_NULL, "y is NULL");
+  if (ldy < down->c.N) return fail(ROSAQ_ERR_SHAPE, "leading dimension smaller than width");
+  if ((static_cast<int64_t>(M) + kMBlock - 1) / kMBlock * kMBlock * down->c.D / 8 > INT32_MAX)
+    return fail(ROSAQ_ERR_SHAPE, "M x in_features above 2^34: split the call");
+  const MlpPlan m = plan_mlp(*gate, *down, M);
+  if (ws_bytes < m.required) return fail(ROSAQ_ERR_WORKSPACE, "workspace missing or too small");
+  const rosaq_packed_t* gu[2] = {gate, up};
+  const rosaq_packed_t* all[3] = {gate, up, down};
+  if (check_device(all, 3) != ROSAQ_OK) return ROSAQ_ERR_HOSTONLY;
+  // 1. xhat of the input (clears the gate / up launch's tickets)
+  if (g_tune_stages & 1) {
+    rc = run_prologue(gate, m.gate, x_dev, M, ldx, ws, m.gate.required, hip_stream);
+    if (rc != ROSAQ_OK) return rc;
+  }
+  if (!(g_tune_stages & 2)) return ROSAQ_OK;
+  // 2. silu(gate) * up, written as down's input fragments at down's storage positions
+  GemmIO io = plan_io(*gate, m.gate, ws, m.gate.required);
+  io.part = nullptr; io.part_bytes = 0;
+  io.chain_pos = down->d_pos; io.chain_ks = down->c.D / kKStep;
+  io.zero_ptr = ws + m.down_tickets; io.zero_count = 2 * kTicketsPerLaunch;
+  void* hs[2] = {ws + m.down_xf, ws + m.down_xf};
+  const int64_t ldh[2] = {0, 0};
+  rc = run_main_gemm(gu, 2, io, M, hs, ldh, hip_stream, true);
+  if (rc != ROSAQ_OK) return rc;
+  // 3. y = h What_down^T
+  GemmIO dn{};
+  dn.xf = ws + m.down_xf;
+  dn.tickets = ws + m.down_tickets + kTicketsPerLaunch * sizeof(uint32_t);
+  dn.part = ws + m.part;
+  dn.part_bytes = ws_bytes > m.part ? ws_bytes - m.part : 0;
+  const int64_t ldys[1] = {ldy};
+  return run_main_gemm(&down, 1, dn, M, &y_dev, ldys, hip_stream);
 }
 
 int rosaq_packed_info(const rosaq_packed_t* p, int32_t* N, int32_t* D, int32_t* K, int32_t* bits,

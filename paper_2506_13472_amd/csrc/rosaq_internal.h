@@ -73,7 +73,9 @@ struct GemmArgs {
   int KS;                // k-steps of the xf operand (D/32)
   int KS_out;            // k-steps of the output when out is in fragment order
   int bits;              // 3 or 4 (ignored when G == 0)
-  int out_frag;          // 0: y row-major, 1: xhat fragment order
+  int out_frag;          // 0: y row-major, 1: xhat fragment order, 2 (gated pair only): input
+                         // fragments of a following layer, channel n at storage position out_pos[n]
+  const void* out_pos = nullptr;   // device int32 [N] for out_frag == 2
   // split-K across workgroups (optional): room for fp32 partial tiles and tile tickets.  A launch
   // is split only if both fit; tickets must be zero before the launch and are zero after it.
   void* part = nullptr;

@@ -123,6 +123,9 @@ struct GemmDev {
   // gated pair (two layers of equal width, unsplit): the tile list alternates layer 0 / layer 1
   // tiles of the same channels, and the epilogue stores silu(layer 0) * layer 1 to seg[0].out
   int swiglu;
+  // gated pair feeding a layer without run-time rotation (out_frag == 2): the product goes
+  // straight into that layer's input fragments, channel n at its storage position out_pos[n]
+  const int* out_pos;
 };
 
 // Partial tiles and tickets travel between workgroups that may sit on different XCDs, whose L2
@@ -519,7 +522,21 @@ void gemm_kernel(GemmDev p) {
   if constexpr (kRedNT % 2 == 0) {
     if (p.swiglu) {
       constexpr int kPairs = (kRedNT / 2) * MT;
+      constexpr int kPairIters = (kPairs + WPB - 1) / WPB;
       const GemmSeg sg = p.seg[0];
+      // storage positions of this wave's output channels in the following layer, requested before
+      // the reduction so that the stores behind it do not wait for them
+      int next_pos[kRedPasses][kPairIters];
+      if (p.out_frag == 2) {
+#pragma unroll
+        for (int pass = 0; pass < kRedPasses; ++pass)
+#pragma unroll
+          for (int it = 0; it < kPairIters; ++it) {
+            const int ps = wave + it * WPB, j = (ps < kPairs ? ps : 0) / MT;
+            const int n = ((tile0 + pass * kRedNT + 2 * j) >> 1) * kTileN + (lane & 15);
+            next_pos[pass][it] = p.out_pos[n < sg.N ? n : 0];
+          }
+      }
 #pragma unroll
       for (int pass = 0; pass < kRedPasses; ++pass) {
         if (pass > 0) __syncthreads();
@@ -531,7 +548,10 @@ void gemm_kernel(GemmDev p) {
             red[wave][nt * MT + mt][lane] = make_float4(v[0], v[1], v[2], v[3]);
           }
         __syncthreads();
-        for (int ps = wave; ps < kPairs; ps += WPB) {
+#pragma unroll
+        for (int it = 0; it < kPairIters; ++it) {
+          const int ps = wave + it * WPB;
+          if (ps >= kPairs) break;
           const int j = ps / MT, mt = ps - j * MT;
           float4 g = red[0][(2 * j) * MT + mt][lane], u = red[0][(2 * j + 1) * MT + mt][lane];
 #pragma unroll
@@ -547,7 +567,18 @@ void gemm_kernel(GemmDev p) {
             for (int i = 0; i < 4; ++i) {
               const int m = (mtile0 + mt) * 16 + 4 * (lane >> 4) + i;
               const float act = gv[i] / (1.0f + __expf(-gv[i]));       // silu
-              if (m < p.M) sg.out[static_cast<int64_t>(m) * sg.ldo + n] = static_cast<_Float16>(act * uv[i]);
+              if (m >= p.M) continue;
+              const _Float16 h = static_cast<_Float16>(act * uv[i]);
+              if (p.out_frag == 2) {
+                // A fragment of the next layer: storage channel np of row m sits in k-step np / 32,
+                // lane 16 ((np / 8) % 4) + m % 16, half np % 8
+                const int np = next_pos[pass][it], mtile = mtile0 + mt;
+                const int lane2 = 4 * (lane >> 4) + i + 16 * ((np >> 3) & 3);
+                sg.out[(((static_cast<size_t>(mtile >> 2) * p.KS_out + (np >> 5)) * 4 + (mtile & 3)) * 64 + lane2) * 8 +
+                       (np & 7)] = h;
+              } else {
+                sg.out[static_cast<int64_t>(m) * sg.ldo + n] = h;
+              }
             }
           }
         }
@@ -1033,6 +1064,7 @@ static int launch_gemm_shape(const GemmArgs& a, const GemmShape& sh, void* strea
   d.ldx = a.ldx;
   d.M = a.M; d.ks_s = a.ks_s; d.G = a.G; d.KS = a.KS; d.KS_out = a.KS_out;
   d.out_frag = a.out_frag;
+  d.out_pos = static_cast<const int*>(a.out_pos);
   d.nseg = a.nseg;
   int tiles = 0;   // valid channel tiles of all layers, in launch order
   for (int i = 0; i < kMaxBatch; ++i) {

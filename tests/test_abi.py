@@ -115,6 +115,42 @@ def test_call_argument_errors_on_host_only_handle():
     p.free(); ph.free()
 
 
+def test_mlp_block_argument_errors_on_host_only_handles():
+    W, Q, lam, K, bits, mode = _good(mode=B.Q_FULL)                      # gate / up: 16 x 256, dense rotation
+    g = B.rosaq_pack_weights(W, Q, lam, K, bits, B.Q_FULL, host_only=True)
+    g3 = B.rosaq_pack_weights(W, Q, lam, K, 3, B.Q_FULL, host_only=True)
+    Wd = np.zeros((48, 128), np.float16)                                   # a down layer would need D = 16
+    d_wide = B.rosaq_pack_weights(Wd, None, np.arange(128.0), 0, bits, B.Q_NONE, host_only=True)
+    W16 = np.zeros((256, 256), np.float16); W16[0, 0] = 1
+    gq = B.rosaq_pack_weights(W16, Q, lam, K, bits, B.Q_FULL, host_only=True)       # 256 -> 256
+    d_ok = B.rosaq_pack_weights(W16, None, lam, K, bits, B.Q_NONE, host_only=True)  # takes 256 channels
+    d_rot = B.rosaq_pack_weights(W16, Q, lam, K, bits, B.Q_FULL, host_only=True)
+    d_abs = B.rosaq_pack_weights(W16, Q, lam, K, bits, B.Q_FULL, host_only=True, rotation_absorbed=True)
+    X, Y, WS = 0x1000, 0x2000, 0x4000      # never dereferenced: every call fails validation first
+    try:
+        n = B.rosaq_workspace_bytes_mlp(gq, gq, d_ok, 4)
+        assert n % 256 == 0 and n > B.rosaq_workspace_bytes_min(gq, 4) + B.rosaq_workspace_bytes_min(d_ok, 4) - 1
+        assert B.rosaq_workspace_bytes_mlp(gq, gq, d_abs, 4) == n          # absorbed rotation: no rotation at run time
+        assert B.rosaq_workspace_bytes_mlp(gq, gq, d_rot, 4) == 0
+        assert B.rosaq_workspace_bytes_mlp(g, g, d_wide, 4) == 0
+        assert B.rosaq_workspace_bytes_mlp(gq, gq, d_ok, 0) == 0
+        assert _code(lambda: B.rosaq_mlp_swiglu(g, g3, d_wide, X, 4, 256, Y, 48, WS, 1 << 30)) == -4   # gate / up differ
+        assert _code(lambda: B.rosaq_mlp_swiglu(g, g, d_wide, X, 4, 256, Y, 48, WS, 1 << 30)) == -2    # width of down
+        assert _code(lambda: B.rosaq_mlp_swiglu(gq, gq, d_rot, X, 4, 256, Y, 256, WS, 1 << 30)) == -4  # down rotates
+        assert _code(lambda: B.rosaq_mlp_swiglu(gq, gq, d_ok, 0, 4, 256, Y, 256, WS, n)) == -1
+        assert _code(lambda: B.rosaq_mlp_swiglu(gq, gq, d_ok, X, 4, 256, 0, 256, WS, n)) == -1
+        assert _code(lambda: B.rosaq_mlp_swiglu(gq, gq, d_ok, X, 0, 256, Y, 256, WS, n)) == -2
+        assert _code(lambda: B.rosaq_mlp_swiglu(gq, gq, d_ok, X, 4, 256, Y, 128, WS, n)) == -2          # ldy < N
+        assert _code(lambda: B.rosaq_mlp_swiglu(gq, gq, d_ok, X, 4, 256, Y, 256, WS,
+                                                B.rosaq_workspace_bytes_min(gq, 4))) == -6                # gate's share only
+        assert _code(lambda: B.rosaq_mlp_swiglu(gq, gq, d_ok, X, 4, 256, Y, 256, WS + 16, n)) == -5
+        assert _code(lambda: B.rosaq_mlp_swiglu(gq, gq, d_ok, X, 4, 256, Y, 256, WS, n)) == -10          # host-only handles
+        assert B.lib().rosaq_mlp_swiglu(None, None, None, X, 4, 256, Y, 256, WS, n, None) == -1
+    finally:
+        for p in (g, g3, d_wide, gq, d_ok, d_rot, d_abs):
+            p.free()
+
+
 def test_tune_keys():
     for k in ("mt", "nt", "wpb"):
         B.rosaq_tune(k, 0)

@@ -90,3 +90,107 @@ def test_swiglu_7b_mlp_full_size():
     finally:
         for p in ps:
             p.free()
+
+
+def run_two_calls(pg, pu, pd, x16):
+    """silu(gate) * up into a row-major buffer, then the down projection as a call of its own."""
+    x = torch.from_numpy(x16).cuda()
+    M = x.shape[0]
+    h = torch.empty((M, pg.N), dtype=torch.float16, device="cuda")
+    ws = T.alloc_workspace(pg, M)
+    B.rosaq_linear_swiglu(pg, pu, x.data_ptr(), M, x.stride(0), h.data_ptr(), h.stride(0),
+                          ws.data_ptr(), ws.numel(), T.current_stream_ptr())
+    y = T.linear(pd, h)
+    torch.cuda.synchronize()
+    return h.cpu().numpy(), y.cpu().numpy()
+
+
+def run_mlp(pg, pu, pd, x16, ws_bytes=None):
+    x = torch.from_numpy(x16).cuda()
+    M = x.shape[0]
+    y = torch.full((M, pd.N), 3.0, dtype=torch.float16, device="cuda")
+    n = B.rosaq_workspace_bytes_mlp(pg, pu, pd, M) if ws_bytes is None else ws_bytes
+    ws = torch.full((n,), 0xA5, dtype=torch.uint8, device="cuda")     # tickets start out dirty
+    B.rosaq_mlp_swiglu(pg, pu, pd, x.data_ptr(), M, x.stride(0), y.data_ptr(), y.stride(0),
+                       ws.data_ptr(), ws.numel(), T.current_stream_ptr())
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+@pytest.mark.parametrize("mode,bits,M,D,F,N,Kd", [(O.MODE_FULL, 4, 64, 512, 384, 200, 128),
+                                                  (O.MODE_HEADWISE, 3, 37, 256, 256, 96, 128),
+                                                  (O.MODE_NONE, 4, 5, 256, 640, 130, 0),
+                                                  (O.MODE_FULL, 4, 150, 384, 1024, 72, 256)])
+def test_mlp_block_equals_the_two_calls_and_the_oracle(mode, bits, M, D, F, N, Kd):
+    """rosaq_mlp_swiglu writes the gated product straight into the down projection's input fragments:
+    bit for bit the result of rosaq_linear_swiglu followed by rosaq_linear, and within the linear
+    layer's tolerance of the oracle's down projection of the fp16 intermediate the GPU produced."""
+    print(f"case mlp block mode={mode} bits={bits} M={M} D={D} F={F} N={N}", flush=True)
+    lay, Q, lam = make_case(320 + M, M, D, F, 300, mode)
+    Wu = (lay["W"][::-1] * np.float16(1.5)).astype(np.float16)
+    down = synth_down(321 + M, N, F)
+    lam_d = np.abs(np.random.default_rng(5).standard_normal(F)) + 0.1      # salient channels scattered
+    ref_d = O.pack(down, None, lam_d, Kd, bits, O.MODE_NONE)
+    pg, pu = (B.rosaq_pack_weights(W, Q, lam, 128, bits, mode) for W in (lay["W"], Wu))
+    pd = B.rosaq_pack_weights(down, None, lam_d, Kd, bits, B.Q_NONE)
+    try:
+        h, y2 = run_two_calls(pg, pu, pd, lay["x"])
+        y = run_mlp(pg, pu, pd, lay["x"])
+        assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
+        # the down launch cut over three workgroups per tile (the gated launch never is): another
+        # summation order, held to the oracle only
+        B.rosaq_tune("splits", 3)
+        try:
+            y_split = run_mlp(pg, pu, pd, lay["x"])
+        finally:
+            B.rosaq_tune("splits", 0)
+        from test_gpu_parity import check_output
+        check_output(y, h, None, ref_d)
+        check_output(y_split, h, None, ref_d)
+    finally:
+        for p in (pg, pu, pd):
+            p.free()
+
+
+def synth_down(seed, N, F):
+    from paper_2506_13472_amd import synth
+    return synth.make_weight(seed, N, F)
+
+
+def test_mlp_block_rejects_what_it_cannot_chain():
+    lay, Q, lam = make_case(340, 8, 256, 256, 300, O.MODE_FULL)
+    g = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_FULL)
+    d_rot = B.rosaq_pack_weights(lay["W"], Q, lam, 128, 4, B.Q_FULL)            # rotates at run time
+    d_narrow = B.rosaq_pack_weights(lay["W"][:, :128].copy(), None, lam[:128], 0, 4, B.Q_NONE)
+    try:
+        for down, code in ((d_rot, "MODE"), (d_narrow, "SHAPE")):
+            with pytest.raises(B.RosaqError) as e:
+                run_mlp(g, g, down, lay["x"], ws_bytes=1 << 24)
+            assert B.ERR_NAMES[e.value.code] == code
+            assert B.rosaq_workspace_bytes_mlp(g, g, down, 8) == 0
+    finally:
+        for p in (g, d_rot, d_narrow):
+            p.free()
+
+
+def test_mlp_block_7b_full_size():
+    """The FFN of a 7B-shaped decode layer at M = 64: 4096 -> 11008 (dense rotation) -> 4096 (no rotation)."""
+    from paper_2506_13472_amd import synth
+    print("case mlp block 7B", flush=True)
+    D, F, M = 4096, 11008, 64
+    Q = synth.random_orthogonal_dense(90, D)
+    lam = synth.descending_spectrum(91, D, 1)
+    x = synth.make_activations(92, M, D)
+    Wg, Wu = (synth.make_weight(93 + j, F, D) for j in range(2))
+    Wd = synth.make_weight(96, D, F)
+    lam_d = np.abs(np.random.default_rng(6).standard_normal(F)) + 0.1
+    pg, pu = (B.rosaq_pack_weights(W, Q, lam, 128, 4, B.Q_FULL) for W in (Wg, Wu))
+    pd = B.rosaq_pack_weights(Wd, None, lam_d, 128, 4, B.Q_NONE)
+    try:
+        h, y2 = run_two_calls(pg, pu, pd, x)
+        y = run_mlp(pg, pu, pd, x)
+        assert np.all(np.isfinite(y))
+        assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
+    finally:
+        for p in (pg, pu, pd):
+            p.free()
