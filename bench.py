@@ -600,10 +600,13 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_sweep:
         rows = []
-        shapes = [s for s in SWEEP_SHAPES if s[0].startswith(BOUNDED_SWEEP)]
-        shape_sweep(torch, shapes, [64], 10, rows.append)
-        out["sweep"] = {"what": "single calls at M = 64 of the INT3 7B MLP and the INT4 13B MLP shapes, K = 128, "
-                                "median of 10 replays of 32 calls over distinct weight copies (cold HBM)",
+        # the INT3 7B MLP at M = 64; the INT4 13B MLP at its whole M sweep (the shape's own list)
+        shape_sweep(torch, [s for s in SWEEP_SHAPES if s[0].startswith("7B") and s[0].startswith(BOUNDED_SWEEP)],
+                    [64], 10, rows.append)
+        shape_sweep(torch, [s for s in SWEEP_SHAPES if s[0].startswith("13B")], None, 10, rows.append)
+        out["sweep"] = {"what": "single calls of the INT3 7B MLP shapes at M = 64 and of the INT4 13B MLP shapes at "
+                                "M = 1, 16, 64, 256 (dense 13824^2 rotation: M = 64), K = 128, median of 10 replays "
+                                "of 32 calls over distinct weight copies (cold HBM)",
                         "rows": rows}
         torch.cuda.empty_cache()
     if not args.no_decode:
