@@ -17,7 +17,7 @@ inputs resident in HBM.  Every step is timed with its own pair of HIP events on 
 stream the kernels run on; median, p10 and p90 are reported (the paper's throughput
 appendix defines decode speed from the median time per token).  The same line carries
 two more measurements, each bounded to a few seconds of GPU time:
-  "sweep"   the M = 64 calls of the INT3 7B MLP and of the INT4 13B MLP (single calls)
+  "sweep"   single calls of the INT3 7B MLP shapes at M = 64 and of the INT4 13B MLP shapes at M = 1, 16, 64, 256
   "decode"  the 7 linears x 32 layers of a 7B-shaped decode step, 256 steps, against fp16 GEMMs
 Weights, activations and the 512-row calibration sets are synthetic (seeded); the head-wise
 rotations are the PCA of the calibration sets, computed on the GPU by rosaq_pca_headwise

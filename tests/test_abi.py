@@ -291,6 +291,18 @@ def test_launch_shape_of_the_named_workloads():
     assert B.ERR_NAMES[e.value.code] == "ARG"
 
 
+def test_bench_traffic_table_holds_the_shapes_the_heuristic_picks():
+    """bench.py reports measured HBM traffic only for launch shapes it has a profile for: the two
+    launches of its default workload must be among them, or the default line would say null."""
+    import importlib.util, os
+    spec = importlib.util.spec_from_file_location("bench", os.path.join(os.path.dirname(__file__), "..", "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    one = (1,) + tuple(B.rosaq_launch_shape(64, 4096, 4096, 4))
+    qkv = (3,) + tuple(B.rosaq_launch_shape(64, 3 * 4096, 4096, 4))
+    assert one in bench.MEASURED_TRAFFIC_KIB and qkv in bench.MEASURED_TRAFFIC_KIB
+
+
 def test_block_map_covers_every_tile_exactly_once():
     """The workgroup -> (channel chunk, row group) map of the main GEMM: a bijection onto the launch's tiles
     plus padding workgroups, with every chunk on the XCD (workgroup % 8) equal to chunk % 8, for all small
